@@ -1,0 +1,271 @@
+"""CPU checker for the replication planner.  TEST INFRASTRUCTURE ONLY.
+
+Pure-Python integers (exact, unbounded), one function per step, in the order the
+paper takes them.  Shares no code with the library's planner; the library never
+imports it.
+
+Steps and where they come from:
+  aggregate_load        Alg. 1, first statement: W_s = W summed over batches.
+  expert_copies         Alg. 1's Placement "number of replicas assigned for each
+                        expert": the paper names it and gives no rule; the reading
+                        here is largest-quotient first (copy to the expert with the
+                        largest load per copy), which minimises the largest
+                        per-copy load.
+  placement             Sec. 4.2.2 step 5: most-loaded expert copy onto the
+                        least-loaded device with free capacity.
+  est_max_rank_load     Alg. 1 inner loops: a copy of e carries floor(W/c_e);
+                        a rank's load is the sum over the copies it holds.
+  greedy_allocation     unit greedy on that cost model: repeatedly add the replica
+                        with the largest reduction of the estimated maximum rank
+                        load per byte until the budget is spent.
+  mckp_allocation       Alg. 2, the paper's exact multiple-choice knapsack DP (used
+                        as a checker for the greedy, and for the paper's objective).
+  capacity_assignment   Alg. 3, interleaved per-layer per-rank expert capacity.
+  make_plan             Sec. 4.2 workflow, steps 3-5, then per-layer reporting
+                        (balancedness = average / maximum rank load, Sec. 3.1).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+
+def aggregate_load(W: Sequence[Sequence[Sequence[int]]]) -> List[List[int]]:
+    """W[b][l][e] -> W_s[l][e]."""
+    B = len(W)
+    L = len(W[0])
+    E = len(W[0][0])
+    return [[sum(int(W[b][l][e]) for b in range(B)) for e in range(E)] for l in range(L)]
+
+
+def expert_copies(ws: Sequence[int], n: int, D: int) -> List[int]:
+    """Copies per expert after handing out n replicas one at a time, each to the
+    expert with the largest load per current copy (exact rational comparison,
+    lowest expert id on ties); an expert never gets more copies than ranks."""
+    E = len(ws)
+    c = [1] * E
+    for _ in range(n):
+        best = -1
+        for e in range(E):
+            if c[e] >= D:
+                continue
+            if best < 0 or ws[e] * c[best] > ws[best] * c[e]:
+                best = e
+        if best < 0:
+            raise ValueError("more replicas than E*(D-1)")
+        c[best] += 1
+    return c
+
+
+def canonical_capacities(total: int, D: int) -> List[int]:
+    """floor(total/D) everywhere, one more on the lowest-numbered total mod D ranks."""
+    return [total // D + (1 if g < total % D else 0) for g in range(D)]
+
+
+def placement(ws: Sequence[int], copies: Sequence[int], cap: Sequence[int]
+              ) -> Tuple[List[List[Tuple[int, int]]], List[int]]:
+    """Greedy placement of expert copies on ranks under per-rank capacities.
+
+    Items are all copies; copy q of expert e weighs floor(ws[e] / copies[e]).
+    Items are taken heaviest first (ties: lower expert, then lower copy).  Each goes
+    to the rank that still has room and does not yet hold a copy of the same expert,
+    with the smallest load so far (ties: more room left, then lower rank id).  If
+    every rank with room already holds that expert, the distinct-rank wish is
+    dropped for this item.  Returns (held[g] = list of (e, q), load[g]).
+    """
+    D = len(cap)
+    E = len(ws)
+    if sum(cap) != sum(copies):
+        raise ValueError("capacities do not add up to the number of copies")
+    items = [(ws[e] // copies[e], e, q) for e in range(E) for q in range(copies[e])]
+    items.sort(key=lambda it: (-it[0], it[1], it[2]))
+    room = list(cap)
+    load = [0] * D
+    held: List[List[Tuple[int, int]]] = [[] for _ in range(D)]
+    has = [set() for _ in range(D)]
+    for wgt, e, q in items:
+        def pick(distinct: bool) -> int:
+            best = -1
+            for g in range(D):
+                if room[g] <= 0 or (distinct and e in has[g]):
+                    continue
+                if best < 0 or (load[g], -room[g]) < (load[best], -room[best]):
+                    best = g
+            return best
+        g = pick(True)
+        if g < 0:
+            g = pick(False)
+        held[g].append((e, q))
+        has[g].add(e)
+        load[g] += wgt
+        room[g] -= 1
+    return held, load
+
+
+def est_max_rank_load(ws: Sequence[int], n: int, D: int) -> int:
+    """M(n): estimated maximum rank load of a layer given n replicas."""
+    E = len(ws)
+    c = expert_copies(ws, n, D)
+    _, load = placement(ws, c, canonical_capacities(E + n, D))
+    return max(load)
+
+
+def greedy_allocation(Ws: Sequence[Sequence[int]], D: int,
+                      bytes_per_replica: Optional[Sequence[int]], budget: int
+                      ) -> Tuple[List[int], List[Tuple[int, int]]]:
+    """Replicas per layer under a byte budget, one replica at a time.
+
+    Each step looks at the layers whose next replica still fits the budget and
+    whose experts are not all at D copies, and picks the one with the largest
+    M(x) - M(x+1) per byte (compared exactly; ties: larger current M, then lower
+    layer).  Steps with no gain are still taken, so the budget is always spent.
+    Returns (x, order) where order lists (layer, spent_after) per step.
+    """
+    L = len(Ws)
+    E = len(Ws[0])
+    by = [1] * L if bytes_per_replica is None else [int(b) for b in bytes_per_replica]
+    if any(b <= 0 for b in by):
+        raise ValueError("bytes_per_replica must be positive")
+    x = [0] * L
+    cur = [est_max_rank_load(Ws[l], 0, D) for l in range(L)]
+    nxt: List[Optional[int]] = [None] * L
+    spent = 0
+    order: List[Tuple[int, int]] = []
+    while True:
+        best = -1
+        for l in range(L):
+            if spent + by[l] > budget or x[l] >= E * (D - 1):
+                continue
+            if nxt[l] is None:
+                nxt[l] = est_max_rank_load(Ws[l], x[l] + 1, D)
+            if best < 0:
+                best = l
+                continue
+            dl, db = cur[l] - nxt[l], cur[best] - nxt[best]
+            lhs, rhs = dl * by[best], db * by[l]
+            if lhs > rhs or (lhs == rhs and cur[l] > cur[best]):
+                best = l
+        if best < 0:
+            break
+        x[best] += 1
+        spent += by[best]
+        cur[best] = nxt[best]
+        nxt[best] = None
+        order.append((best, spent))
+    return x, order
+
+
+def mckp_allocation(Tmap: Dict[int, Sequence[float]], C: int) -> List[int]:
+    """Alg. 2: one replica count per layer from {0} + keys(T), total exactly C,
+    maximum total gain.  Keys are visited in ascending order and a candidate
+    replaces the incumbent only when strictly better.  Returns x, or raises when
+    no selection sums to C."""
+    keys = sorted(Tmap.keys())
+    L = len(Tmap[keys[0]])
+    NEG = None
+    dp = [[NEG] * (C + 1) for _ in range(L + 1)]
+    choice = [[None] * (C + 1) for _ in range(L + 1)]
+    dp[0][0] = 0
+    for l in range(1, L + 1):
+        j = l - 1
+        for c in range(C + 1):
+            dp[l][c] = dp[l - 1][c]
+            choice[l][c] = None
+            for r in keys:
+                if c >= r and dp[l - 1][c - r] is not NEG:
+                    cand = dp[l - 1][c - r] + Tmap[r][j]
+                    if dp[l][c] is NEG or cand > dp[l][c]:
+                        dp[l][c] = cand
+                        choice[l][c] = r
+    if dp[L][C] is NEG:
+        raise ValueError("no selection of replica counts sums to C")
+    x = [0] * L
+    c = C
+    for l in range(L, 0, -1):
+        r = choice[l][c]
+        if r is not None:
+            x[l - 1] = r
+            c -= r
+    return x
+
+
+def interleave_select(idx: Sequence[int], k: int) -> List[int]:
+    """k entries of idx, evenly spread: positions floor(i * len / k), i = 0..k-1.
+
+    This is the spacing of the paper's worked example (Sec. 4.2.2: four tied
+    devices, two extras -> devices 0 and 2), which the example fixes more firmly
+    than the one-line description of the helper in Alg. 3."""
+    n = len(idx)
+    return [idx[(i * n) // k] for i in range(k)]
+
+
+def capacity_assignment(D: int, R: Sequence[int]) -> List[List[int]]:
+    """Alg. 3.  R[l] = physical experts (base + replicas) of layer l.
+    Returns A[l][g] = experts held by rank g in layer l."""
+    L = len(R)
+    A = [[R[l] // D] * D for l in range(L)]
+    G = [sum(A[l][g] for l in range(L)) for g in range(D)]
+    for l in range(L):
+        r = R[l] % D
+        if r == 0:
+            continue
+        cutoff = sorted(G)[r - 1]
+        M = [g for g in range(D) if G[g] < cutoff]
+        q = r - len(M)
+        if q > 0:
+            K = sorted(g for g in range(D) if G[g] == cutoff)
+            S = M + interleave_select(K, q)
+        else:
+            S = M
+        for g in S:
+            A[l][g] += 1
+            G[g] += 1
+    return A
+
+
+def layer_tables(held: Sequence[Sequence[Tuple[int, int]]]) -> Tuple[List[int], List[int]]:
+    """Slot numbering of one layer: rank-major, within a rank by (expert, copy).
+    Returns (slot_expert[S], rank_slot_off[D+1])."""
+    slot_expert: List[int] = []
+    off = [0]
+    for g in range(len(held)):
+        for e, _q in sorted(held[g]):
+            slot_expert.append(e)
+        off.append(len(slot_expert))
+    return slot_expert, off
+
+
+def make_plan(W, D: int, bytes_per_replica: Optional[Sequence[int]], budget: int) -> dict:
+    """The whole planner.  W[b][l][e] integer loads."""
+    Ws = aggregate_load(W)
+    L, E = len(Ws), len(Ws[0])
+    x, order = greedy_allocation(Ws, D, bytes_per_replica, budget)
+    A = capacity_assignment(D, [E + x[l] for l in range(L)])
+    layers = []
+    for l in range(L):
+        c = expert_copies(Ws[l], x[l], D)
+        held, load = placement(Ws[l], c, A[l])
+        slot_expert, off = layer_tables(held)
+        mx = max(load)
+        bal = 1.0 if mx == 0 else (sum(load) / D) / mx
+        layers.append(dict(n_replicas=x[l], copies=c, slot_expert=slot_expert,
+                           rank_slot_off=off, capacity=A[l], rank_load=load,
+                           est_max_rank_load=mx, est_balancedness=bal))
+    total = sum(x)
+    return dict(L=L, E=E, D=D, x=x, order=order, layers=layers, total_replicas=total,
+                replication_factor=total / D,
+                memory_saving_vs_uniform=(L * D / total) if total else float("inf"))
+
+
+def realized_rank_rows(slot_cnt: Sequence[int], rank_slot_off: Sequence[int]) -> List[int]:
+    """Rows each rank executes for a dispatched batch (sum of its slots' counts)."""
+    return [sum(slot_cnt[rank_slot_off[g]:rank_slot_off[g + 1]])
+            for g in range(len(rank_slot_off) - 1)]
+
+
+def heaviest_rank(rows: Sequence[int]) -> int:
+    """The rank with the most rows; the lowest-numbered one on ties."""
+    best = 0
+    for g in range(1, len(rows)):
+        if rows[g] > rows[best]:
+            best = g
+    return best
