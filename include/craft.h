@@ -1,0 +1,234 @@
+/*
+ * craft.h -- C ABI of libcraft: one expert-parallel rank's MoE layer under a CRAFT
+ * replication plan, on one MI355X (gfx950).
+ *
+ * The calls follow the paper's statement of the problem:
+ *   load profiling  (Sec. 2.3, Sec. 3.1 "expert load", Alg. 1 input W[B][L][E])
+ *   planning        (Sec. 4.2 workflow steps 3-5, Alg. 1 cost model, Alg. 2, Alg. 3)
+ *   execution       (Sec. 2.1: router top-K, expert FFN, weighted sum; Sec. 1: a
+ *                    replicated expert's tokens are spread over its copies)
+ *
+ * Conventions
+ *   - Plain C types only.  Every pointer is marked HOST or DEVICE.  The caller owns
+ *     every buffer; the library allocates only the plan object (host memory, released
+ *     by craft_plan_destroy) and never allocates or frees device memory.
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = the null stream).
+ *     Device entry points only enqueue work: they return after launching, do not
+ *     synchronise, and report launch-time errors as CRAFT_EHIP.  Faults inside a kernel
+ *     surface at the caller's next synchronisation.
+ *   - Every call returns a craft_status; nothing is thrown across the boundary.
+ *   - Router scores must be finite (NaN is not detected; the result is then unspecified).
+ *   - Row-major everywhere; [a][b] means b is contiguous.
+ */
+#ifndef CRAFT_H
+#define CRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CRAFT_OK = 0,
+    CRAFT_EINVAL = -1,      /* bad argument (NULL, size out of range, misaligned, unknown table) */
+    CRAFT_ENOMEM = -2,      /* host allocation failed */
+    CRAFT_EHIP = -3,        /* a HIP runtime call or kernel launch failed */
+    CRAFT_EWORKSPACE = -4,  /* workspace or table buffer too small */
+    CRAFT_EINFEASIBLE = -5  /* the request cannot be met (e.g. more replicas than E*(D-1)) */
+} craft_status;
+
+const char *craft_status_str(craft_status s);
+
+/* Element types of activations and expert weights. */
+enum { CRAFT_F32 = 0, CRAFT_BF16 = 1 };
+
+/* ------------------------------------------------------------------ routing
+ * Sec. 2.1: the gating network's scores select the top-K experts of each token.
+ *   logits  DEVICE [T][E] fp32 router scores
+ *   ids     DEVICE [T][k] int32: expert with the (j+1)-th largest score (equal scores:
+ *           lower expert id first)
+ *   w       DEVICE [T][k] fp32: softmax probability of that expert over all E scores;
+ *           divided by the sum over the k picked when renormalize != 0
+ * Limits: 1 <= k <= E <= 1024, k <= 64.  T may be 0.
+ */
+craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t k,
+                              int32_t renormalize, int32_t *ids, float *w, void *stream);
+
+/* ------------------------------------------------------------- load profiling
+ * Sec. 3.1: expert load = tokens dispatched to an expert after routing, recorded over
+ * batch x layer x expert (the W of Alg. 1).
+ *   topk_ids      DEVICE [L][T][k] int32 routing trace; every id must lie in [0, E):
+ *                 ids outside are not counted and make the call's result unspecified
+ *   batch_tokens  tokens per profiling batch; B = ceil(T / batch_tokens)
+ *   counts        DEVICE [B][L][E] int64, fully overwritten
+ * Limits: E <= 4096.
+ */
+craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, int32_t k,
+                               int32_t E, int64_t batch_tokens, int64_t *counts, void *stream);
+
+/* -------------------------------------------------------------------- planning
+ * Host-side.  Decides how many replicas each layer gets under a memory budget, which
+ * experts are copied, how many experts each rank holds per layer (Alg. 3) and which rank
+ * holds which copy (Sec. 4.2.2 greedy placement).
+ *
+ * objective 0 (default): one replica at a time to the layer with the largest reduction of
+ *   the estimated maximum rank load per byte, until no further replica fits the budget.
+ *   The estimate is Alg. 1's model on the aggregated load: a copy of expert e carries
+ *   floor(W_s[e] / copies[e]) and a rank's load is the sum over the copies it holds.
+ * objective 1: the paper's own pipeline -- Alg. 1 replays every batch for replica counts
+ *   1,2,4,..,D to get per-layer balancedness gains, Alg. 2 picks one count per layer by
+ *   dynamic programming so that the counts sum to budget_bytes / bytes_per_replica
+ *   (all layers must then share one replica size).
+ */
+typedef struct craft_plan craft_plan_t;
+
+typedef struct {
+    int32_t L;                 /* MoE layers */
+    int32_t E;                 /* logical experts per layer */
+    int32_t D;                 /* expert-parallel ranks */
+    int32_t gpus_per_node;     /* carried in the plan; placement is node-agnostic */
+    int64_t B;                 /* profiling batches */
+    const int64_t *load;       /* HOST [B][L][E] token counts, all >= 0 */
+    const int64_t *bytes_per_replica; /* HOST [L], each > 0; NULL = 1 everywhere */
+    int64_t budget_bytes;      /* total over all layers and ranks, >= 0 */
+    int32_t objective;         /* 0 or 1, see above */
+} craft_plan_params;
+
+craft_status craft_plan(const craft_plan_params *params, craft_plan_t **out);
+void craft_plan_destroy(craft_plan_t *plan);
+
+/* Whole-plan summary: total replicas, replication factor R = total / D, and the memory
+ * saving against uniform replication, L*D / total (Sec. 5.2; +inf when total is 0). */
+craft_status craft_plan_summary(const craft_plan_t *plan, int32_t *L, int32_t *E, int32_t *D,
+                                int64_t *total_replicas, double *replication_factor,
+                                double *memory_saving_vs_uniform);
+
+/* Per-layer figures.  est_balancedness = average / maximum estimated rank load (Sec. 3.1). */
+craft_status craft_plan_layer_info(const craft_plan_t *plan, int32_t layer, int32_t *n_replicas,
+                                   int32_t *n_slots, double *est_balancedness,
+                                   int64_t *est_max_rank_load);
+
+/* Per-layer tables, copied into caller HOST buffers (any may be NULL):
+ *   copies        [E]    copies of each expert (1 + its replicas)
+ *   slot_expert   [S]    expert held by each physical slot, S = E + n_replicas; slots are
+ *                        numbered rank-major, within a rank by ascending expert id
+ *   rank_slot_off [D+1]  first slot of each rank
+ *   rank_load     [D]    estimated load of each rank
+ */
+craft_status craft_plan_layer_tables(const craft_plan_t *plan, int32_t layer, int32_t *copies,
+                                     int32_t *slot_expert, int32_t *rank_slot_off,
+                                     int64_t *rank_load);
+
+/* The order in which objective 0 handed out replicas: step i gave one replica to
+ * layers[i].  Returns the number of steps in *n; copies min(*n, cap) entries. */
+craft_status craft_plan_greedy_order(const craft_plan_t *plan, int32_t *layers, int64_t cap,
+                                     int64_t *n);
+
+/* Rows each rank would execute for a batch with the given per-expert token counts under
+ * the plan's dispatch rule (the i-th token of expert e goes to copy i mod copies[e]).
+ *   counts HOST [E];  rows HOST [D];  heaviest = rank with most rows (lowest id on ties). */
+craft_status craft_plan_rank_rows(const craft_plan_t *plan, int32_t layer, const int64_t *counts,
+                                  int64_t *rows, int32_t *heaviest);
+
+/* Device copy of the tables one rank's forward needs.  Query the size, let the caller
+ * allocate DEVICE memory (256-byte aligned), upload once, and pass the pointer to every
+ * forward of that (plan, layer, rank).  The plan remembers which buffers it filled; a
+ * forward given any other pointer returns CRAFT_EINVAL.  The upload is enqueued on
+ * `stream` from pageable host memory owned by the plan. */
+craft_status craft_plan_tables_bytes(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                     size_t *bytes);
+craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,
+                                      void *dev_tables, size_t bytes, void *stream);
+
+/* ------------------------------------------------------------------- execution
+ * One rank's share of one MoE layer (Sec. 2.1) under the plan:
+ *   1 route       ids, w = top-k of logits                         (as craft_route_topk)
+ *   2 load        counts[e] = assignments naming expert e
+ *   3 dispatch    assignment a = t*k+j, the i-th naming expert e, goes to that expert's
+ *                 copy (i mod copies[e]); dest[a] = position in the slot-ordered
+ *                 permutation, src = inverse of dest
+ *   4 expert FFN  for each slot of this rank, rows R of its tokens:
+ *                 Y = (silu(R Wg^T) * (R Wu^T)) Wd^T, fp32 accumulation
+ *   5 combine     out[t] = sum over this rank's assignments of token t, j ascending, of
+ *                 w[t][j] * Y[row of (t,j)]; tokens with none get zeros
+ *
+ *   x        DEVICE [T][H] activations, dtype
+ *   logits   DEVICE [T][E] fp32
+ *   w_gate, w_up  DEVICE arrays of s device pointers, one per slot of this rank in slot
+ *                 order, each to a [I][H] matrix of dtype
+ *   w_down        likewise, each [H][I]
+ *   out      DEVICE [T][H] dtype, fully overwritten
+ *   ids, topk_w, dest, src  optional DEVICE outputs [T][k] (int32/fp32/int32/int32);
+ *                 NULL = kept in the workspace only
+ *   counts   optional DEVICE output [E] int32
+ *   slot_cnt, slot_off  optional DEVICE outputs [S] / [S+1] int32 over all slots
+ *   max_rows rows the staging buffers are sized for.  0 = the worst case
+ *            T * min(k, s).  If the batch routes more rows than this to the rank the
+ *            forward does no FFN work, zero-fills out and sets the overflow flag.
+ *   workspace DEVICE, 256-byte aligned, at least craft_moe_rank_forward_workspace() bytes.
+ *            Forwards that share a workspace must be ordered on one stream.
+ * Alignment: x, out and all weight matrices 16-byte aligned; H % 8 == 0 and I % 8 == 0
+ * for bf16 (H % 4, I % 4 for fp32).
+ * Limits: T*k < 2^31, k <= 64, E <= 1024, slots of one rank <= 1024.
+ */
+typedef struct {
+    int32_t dtype;
+    int64_t T;
+    int32_t H, I, k;
+    int32_t renormalize;
+    const void *x;
+    const float *logits;
+    const void *const *w_gate;
+    const void *const *w_up;
+    const void *const *w_down;
+    void *out;
+    int32_t *ids;
+    float *topk_w;
+    int32_t *dest;
+    int32_t *src;
+    int32_t *counts;
+    int32_t *slot_cnt;
+    int32_t *slot_off;
+    int64_t max_rows;
+    const void *tables;        /* from craft_plan_tables_upload */
+    void *workspace;
+    size_t workspace_bytes;
+} craft_fwd_args;
+
+craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t layer,
+                                              int32_t rank, const craft_fwd_args *args,
+                                              size_t *bytes);
+craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                    const craft_fwd_args *args, void *stream);
+
+/* After the caller has synchronised the stream: what the last forward on this workspace
+ * found.  rows = rows routed to the rank; overflow != 0 when rows > max_rows (nothing was
+ * computed).  Copies 16 bytes from the device, synchronously. */
+craft_status craft_moe_rank_forward_result(const void *workspace, int64_t *rows,
+                                           int32_t *overflow);
+
+/* ------------------------------------------------------------ kernel timing
+ * Optional HIP-event timing of the kernels inside craft_moe_rank_forward, recorded on the
+ * stream the kernels run on.  level 0 = off, 1 = the grouped gate/up GEMM only, 2 = every
+ * kernel.  Events come from a pool created here (max_forwards forwards can be recorded
+ * between two reads).  craft_timing_read synchronises the recorded events, returns the
+ * summed milliseconds and the number of launches per kernel, and rewinds the pool.
+ */
+enum {
+    CRAFT_K_ROUTE = 0,     /* top-k + per-block ranks */
+    CRAFT_K_SCAN = 1,      /* per-expert scan, slot offsets, tile table */
+    CRAFT_K_DISPATCH = 2,  /* dest / src */
+    CRAFT_K_GATEUP = 3,    /* grouped gate/up GEMM + SwiGLU (gathers its rows) */
+    CRAFT_K_DOWN = 4,      /* grouped down GEMM */
+    CRAFT_K_COMBINE = 5,   /* weighted combine */
+    CRAFT_K_COUNT = 6
+};
+craft_status craft_timing_enable(int32_t level, int32_t max_forwards);
+craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_K_COUNT]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CRAFT_H */

@@ -1,0 +1,302 @@
+"""Thin ctypes binding over libcraft.so: argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels (or, for the planner, its
+host C++).  PyTorch is used for device memory and streams only.  There is no fallback: if
+the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcraft.so")
+
+CRAFT_F32, CRAFT_BF16 = 0, 1
+KERNEL_NAMES = ["route", "scan", "dispatch", "gateup", "down", "combine"]
+
+c_i32, c_i64, c_vp, c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+P = ctypes.POINTER
+
+
+class PlanParams(ctypes.Structure):
+    _fields_ = [("L", c_i32), ("E", c_i32), ("D", c_i32), ("gpus_per_node", c_i32), ("B", c_i64),
+                ("load", c_vp), ("bytes_per_replica", c_vp), ("budget_bytes", c_i64),
+                ("objective", c_i32)]
+
+
+class FwdArgs(ctypes.Structure):
+    _fields_ = [("dtype", c_i32), ("T", c_i64), ("H", c_i32), ("I", c_i32), ("k", c_i32),
+                ("renormalize", c_i32), ("x", c_vp), ("logits", c_vp), ("w_gate", c_vp),
+                ("w_up", c_vp), ("w_down", c_vp), ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
+                ("dest", c_vp), ("src", c_vp), ("counts", c_vp), ("slot_cnt", c_vp),
+                ("slot_off", c_vp), ("max_rows", c_i64), ("tables", c_vp), ("workspace", c_vp),
+                ("workspace_bytes", c_sz)]
+
+
+EXPORTS = {
+    "craft_status_str": (ctypes.c_char_p, [ctypes.c_int]),
+    "craft_route_topk": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp]),
+    "craft_expert_load": (ctypes.c_int, [c_vp, c_i32, c_i64, c_i32, c_i32, c_i64, c_vp, c_vp]),
+    "craft_plan": (ctypes.c_int, [P(PlanParams), P(c_vp)]),
+    "craft_plan_destroy": (None, [c_vp]),
+    "craft_plan_summary": (ctypes.c_int, [c_vp, P(c_i32), P(c_i32), P(c_i32), P(c_i64),
+                                          P(ctypes.c_double), P(ctypes.c_double)]),
+    "craft_plan_layer_info": (ctypes.c_int, [c_vp, c_i32, P(c_i32), P(c_i32), P(ctypes.c_double),
+                                             P(c_i64)]),
+    "craft_plan_layer_tables": (ctypes.c_int, [c_vp, c_i32, c_vp, c_vp, c_vp, c_vp]),
+    "craft_plan_greedy_order": (ctypes.c_int, [c_vp, c_vp, c_i64, P(c_i64)]),
+    "craft_plan_rank_rows": (ctypes.c_int, [c_vp, c_i32, c_vp, c_vp, P(c_i32)]),
+    "craft_plan_tables_bytes": (ctypes.c_int, [c_vp, c_i32, c_i32, P(c_sz)]),
+    "craft_plan_tables_upload": (ctypes.c_int, [c_vp, c_i32, c_i32, c_vp, c_sz, c_vp]),
+    "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
+    "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
+    "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
+    "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
+    "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
+}
+
+_lib = None
+
+
+class CraftError(RuntimeError):
+    pass
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise CraftError(f"{LIB_PATH} is missing: build it first "
+                             "(python -m paper_2603_28768_amd.build)")
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            f = getattr(l, name)
+            f.restype, f.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise CraftError(f"{what}: {lib().craft_status_str(rc).decode()} ({rc})")
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t):
+    """Device pointer of a CUDA tensor (or NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return ctypes.c_void_p(t.data_ptr())
+
+
+# ------------------------------------------------------------------------ routing
+
+def route_topk(logits, k: int, renormalize: bool = True, stream=None):
+    """logits: cuda float32 [T][E] -> (ids int32 [T][k], w float32 [T][k])."""
+    import torch
+    assert logits.dtype == torch.float32 and logits.dim() == 2
+    T, E = logits.shape
+    ids = torch.empty((T, k), dtype=torch.int32, device=logits.device)
+    w = torch.empty((T, k), dtype=torch.float32, device=logits.device)
+    _check(lib().craft_route_topk(_dev(logits), T, E, k, int(renormalize), _dev(ids), _dev(w),
+                                  _stream_ptr(stream)), "craft_route_topk")
+    return ids, w
+
+
+def expert_load(topk_ids, E: int, batch_tokens: int, stream=None):
+    """topk_ids: cuda int32 [L][T][k] -> counts cuda int64 [B][L][E]."""
+    import torch
+    assert topk_ids.dtype == torch.int32 and topk_ids.dim() == 3
+    L, T, k = topk_ids.shape
+    B = (T + batch_tokens - 1) // batch_tokens
+    counts = torch.empty((B, L, E), dtype=torch.int64, device=topk_ids.device)
+    _check(lib().craft_expert_load(_dev(topk_ids), L, T, k, E, batch_tokens, _dev(counts),
+                                   _stream_ptr(stream)), "craft_expert_load")
+    return counts
+
+
+# ----------------------------------------------------------------------- planning
+
+class Plan:
+    """Owner of a craft_plan_t."""
+
+    def __init__(self, load: np.ndarray, D: int, budget_bytes: int,
+                 bytes_per_replica: Optional[Sequence[int]] = None, gpus_per_node: int = 8,
+                 objective: int = 0):
+        load = np.ascontiguousarray(load, dtype=np.int64)
+        assert load.ndim == 3
+        B, L, E = load.shape
+        bpr = None if bytes_per_replica is None else np.ascontiguousarray(bytes_per_replica, np.int64)
+        pp = PlanParams(L, E, D, gpus_per_node, B, load.ctypes.data,
+                        None if bpr is None else bpr.ctypes.data, int(budget_bytes), objective)
+        h = c_vp()
+        _check(lib().craft_plan(ctypes.byref(pp), ctypes.byref(h)), "craft_plan")
+        self._h = h
+        self.L, self.E, self.D = L, E, D
+        self._keep = []          # device table buffers stay alive with the plan
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h is not None and _lib is not None:
+            _lib.craft_plan_destroy(h)
+
+    def summary(self) -> dict:
+        L, E, D = c_i32(), c_i32(), c_i32()
+        tot, rf, ms = c_i64(), ctypes.c_double(), ctypes.c_double()
+        _check(lib().craft_plan_summary(self._h, L, E, D, tot, rf, ms), "craft_plan_summary")
+        return dict(L=L.value, E=E.value, D=D.value, total_replicas=tot.value,
+                    replication_factor=rf.value, memory_saving_vs_uniform=ms.value)
+
+    def layer(self, layer: int) -> dict:
+        n, S, bal, mx = c_i32(), c_i32(), ctypes.c_double(), c_i64()
+        _check(lib().craft_plan_layer_info(self._h, layer, n, S, bal, mx), "craft_plan_layer_info")
+        copies = np.empty(self.E, np.int32)
+        slot_expert = np.empty(S.value, np.int32)
+        off = np.empty(self.D + 1, np.int32)
+        load = np.empty(self.D, np.int64)
+        _check(lib().craft_plan_layer_tables(self._h, layer, copies.ctypes.data,
+                                             slot_expert.ctypes.data, off.ctypes.data,
+                                             load.ctypes.data), "craft_plan_layer_tables")
+        return dict(n_replicas=n.value, n_slots=S.value, est_balancedness=bal.value,
+                    est_max_rank_load=mx.value, copies=copies, slot_expert=slot_expert,
+                    rank_slot_off=off, rank_load=load)
+
+    def greedy_order(self) -> np.ndarray:
+        n = c_i64()
+        _check(lib().craft_plan_greedy_order(self._h, None, 0, n), "craft_plan_greedy_order")
+        out = np.empty(n.value, np.int32)
+        _check(lib().craft_plan_greedy_order(self._h, out.ctypes.data, n.value, n),
+               "craft_plan_greedy_order")
+        return out
+
+    def rank_rows(self, layer: int, counts: np.ndarray):
+        counts = np.ascontiguousarray(counts, dtype=np.int64)
+        assert counts.shape == (self.E,)
+        rows = np.empty(self.D, np.int64)
+        top = c_i32()
+        _check(lib().craft_plan_rank_rows(self._h, layer, counts.ctypes.data, rows.ctypes.data, top),
+               "craft_plan_rank_rows")
+        return rows, top.value
+
+    def upload_tables(self, layer: int, rank: int, device="cuda:0", stream=None):
+        """Device tensor holding the tables of (layer, rank)."""
+        import torch
+        n = c_sz()
+        _check(lib().craft_plan_tables_bytes(self._h, layer, rank, n), "craft_plan_tables_bytes")
+        buf = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+        _check(lib().craft_plan_tables_upload(self._h, layer, rank, _dev(buf), n.value,
+                                              _stream_ptr(stream)), "craft_plan_tables_upload")
+        self._keep.append(buf)
+        return buf
+
+
+# ---------------------------------------------------------------------- execution
+
+def _torch_dtype(dtype: str):
+    import torch
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda:0"):
+    """Host float32 values (already representable in `dtype`) -> device tensor of `dtype`."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    return t.to(device=device, dtype=_torch_dtype(dtype)).contiguous()
+
+
+class RankForward:
+    """Buffers and argument block for repeated forwards of one (plan, layer, rank)."""
+
+    def __init__(self, plan: Plan, layer: int, rank: int, dtype: str, T: int, H: int, I: int,
+                 k: int, w_gate: Sequence, w_up: Sequence, w_down: Sequence,
+                 renormalize: bool = True, max_rows: int = 0, device="cuda:0",
+                 want_debug_outputs: bool = False):
+        import torch
+        self.plan, self.layer, self.rank = plan, layer, rank
+        self.dtype, self.T, self.H, self.I, self.k = dtype, T, H, I, k
+        info = plan.layer(layer)
+        self.S = info["n_slots"]
+        off = info["rank_slot_off"]
+        self.nslots = int(off[rank + 1] - off[rank])
+        assert len(w_gate) == len(w_up) == len(w_down) == self.nslots
+        td = _torch_dtype(dtype)
+        for wg, wu, wd in zip(w_gate, w_up, w_down):
+            assert wg.dtype == td and tuple(wg.shape) == (I, H) and wg.is_contiguous()
+            assert wu.dtype == td and tuple(wu.shape) == (I, H) and wu.is_contiguous()
+            assert wd.dtype == td and tuple(wd.shape) == (H, I) and wd.is_contiguous()
+        self._weights = (list(w_gate), list(w_up), list(w_down))
+        mk = lambda ws: torch.tensor([w.data_ptr() for w in ws] or [0], dtype=torch.int64,
+                                     device=device)
+        self._ptrs = (mk(w_gate), mk(w_up), mk(w_down))
+        self.tables = plan.upload_tables(layer, rank, device)
+        self.out = torch.empty((T, H), dtype=td, device=device)
+        self.debug = {}
+        if want_debug_outputs:
+            i32 = dict(dtype=torch.int32, device=device)
+            self.debug = dict(ids=torch.empty((T, k), **i32),
+                              topk_w=torch.empty((T, k), dtype=torch.float32, device=device),
+                              dest=torch.empty((T, k), **i32), src=torch.empty((T * k,), **i32),
+                              counts=torch.empty((plan.E,), **i32),
+                              slot_cnt=torch.empty((self.S,), **i32),
+                              slot_off=torch.empty((self.S + 1,), **i32))
+        a = FwdArgs()
+        a.dtype = CRAFT_BF16 if dtype == "bf16" else CRAFT_F32
+        a.T, a.H, a.I, a.k = T, H, I, k
+        a.renormalize = int(renormalize)
+        a.w_gate, a.w_up, a.w_down = (p.data_ptr() for p in self._ptrs)
+        a.out = self.out.data_ptr()
+        for name, t in self.debug.items():
+            setattr(a, name, t.data_ptr())
+        a.max_rows = max_rows
+        a.tables = self.tables.data_ptr()
+        n = c_sz()
+        _check(lib().craft_moe_rank_forward_workspace(plan._h, layer, rank, ctypes.byref(a), n),
+               "craft_moe_rank_forward_workspace")
+        self.workspace = torch.empty(n.value + 256, dtype=torch.uint8, device=device)
+        a.workspace = self.workspace.data_ptr()
+        a.workspace_bytes = n.value
+        self.args = a
+
+    def __call__(self, x, logits, stream=None):
+        """Enqueue one forward; returns the (reused) output tensor."""
+        import torch
+        assert x.dtype == _torch_dtype(self.dtype) and tuple(x.shape) == (self.T, self.H)
+        assert logits.dtype == torch.float32 and tuple(logits.shape) == (self.T, self.plan.E)
+        assert x.is_contiguous() and logits.is_contiguous()
+        self.args.x = x.data_ptr()
+        self.args.logits = logits.data_ptr()
+        _check(lib().craft_moe_rank_forward(self.plan._h, self.layer, self.rank,
+                                            ctypes.byref(self.args), _stream_ptr(stream)),
+               "craft_moe_rank_forward")
+        return self.out
+
+    def result(self):
+        """(rows routed to the rank, overflow flag) of the last forward; synchronises."""
+        import torch
+        torch.cuda.synchronize()
+        rows, ovf = c_i64(), c_i32()
+        _check(lib().craft_moe_rank_forward_result(_dev(self.workspace), rows, ovf),
+               "craft_moe_rank_forward_result")
+        return rows.value, ovf.value
+
+
+def timing_enable(level: int, max_forwards: int = 0):
+    _check(lib().craft_timing_enable(level, max_forwards), "craft_timing_enable")
+
+
+def timing_read() -> dict:
+    ms = (ctypes.c_double * len(KERNEL_NAMES))()
+    n = (c_i64 * len(KERNEL_NAMES))()
+    _check(lib().craft_timing_read(ms, n), "craft_timing_read")
+    return {name: dict(ms=ms[i], launches=n[i]) for i, name in enumerate(KERNEL_NAMES)}

@@ -1,0 +1,104 @@
+// Gather-weighted combine (Sec. 2.1: the activated experts' outputs are aggregated into a
+// weighted sum).  One 64-lane wavefront per token; a lane owns 16-byte column chunks of the
+// row.  Only assignments whose dispatched position falls inside this rank's row range
+// contribute, added in ascending j with fp32 accumulation; there are no atomics, so the
+// result does not depend on scheduling.  Tokens with no assignment on the rank get zeros.
+#include <hip/hip_bf16.h>
+
+#include "kernels.h"
+
+namespace craft {
+namespace {
+
+template <typename T> struct Chunk;
+template <> struct Chunk<float> {
+    static constexpr int N = 4;
+    __device__ static void load(const float *p, float (&v)[4]) {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    __device__ static void store(float *p, const float (&v)[4]) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct Chunk<__hip_bfloat16> {
+    static constexpr int N = 8;
+    __device__ static void load(const __hip_bfloat16 *p, float (&v)[8]) {
+        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static uint32_t rne(float f) {       // fp32 -> bf16 bits, nearest even
+        const uint32_t u = __float_as_uint(f);
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    __device__ static void store(__hip_bfloat16 *p, const float (&v)[8]) {
+        uint4 q;
+        q.x = rne(v[0]) | (rne(v[1]) << 16);
+        q.y = rne(v[2]) | (rne(v[3]) << 16);
+        q.z = rne(v[4]) | (rne(v[5]) << 16);
+        q.w = rne(v[6]) | (rne(v[7]) << 16);
+        *reinterpret_cast<uint4 *>(p) = q;
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+    constexpr int N = Chunk<T>::N;
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= a.T) return;
+    const int32_t lo = a.slot_off[a.s_lo], hi = a.slot_off[a.s_hi];
+    const bool dead = a.ctrl[CTRL_OVERFLOW] != 0;
+    int32_t d = -1;
+    float wj = 0.0f;
+    if (lane < a.k) {
+        d = a.dest[t * a.k + lane];
+        wj = a.w[t * a.k + lane];
+    }
+    const bool mine = !dead && lane < a.k && d >= lo && d < hi;
+    const unsigned long long live = __ballot(mine);
+    const T *y = static_cast<const T *>(a.y);
+    T *out = static_cast<T *>(a.out) + t * a.H;
+    // the chunk loop is uniform over the wave (shuffles need every lane); a lane past the end
+    // of the row only skips its loads and its store
+    for (int base = 0; base < a.H; base += 64 * N) {
+        const int c0 = base + lane * N;
+        const bool inside = c0 < a.H;
+        float acc[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = 0.0f;
+        unsigned long long m = live;
+        while (m) {
+            const int j = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const int32_t dj = __shfl(d, j, 64);
+            const float wv = __shfl(wj, j, 64);
+            if (inside) {
+                float v[N];
+                Chunk<T>::load(y + (int64_t)(dj - lo) * a.H + c0, v);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[i] += wv * v[i];
+            }
+        }
+        if (inside) Chunk<T>::store(out + c0, acc);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_combine(const CombineArgs &a, hipStream_t s) {
+    if (a.T == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)((a.T + 3) / 4);
+    if (a.dtype == CRAFT_F32)
+        hipLaunchKernelGGL(combine_kernel<float>, dim3(blocks), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(combine_kernel<__hip_bfloat16>, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace craft

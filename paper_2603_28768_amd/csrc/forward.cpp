@@ -1,0 +1,288 @@
+// Device-side entry points of the C ABI: argument checks, workspace layout, launches.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "kernels.h"
+
+namespace {
+
+using namespace craft;
+
+inline hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- workspace layout of one forward -------------------------------------------------
+struct Layout {
+    size_t ctrl, ids, w, lrank, dest, src, hist, counts, slot_cnt, slot_off, mt_start, act, y, total;
+    int64_t max_rows, NB;
+};
+
+Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, int32_t H, int32_t I,
+                   int32_t dtype, int64_t max_rows_arg) {
+    Layout L;
+    const int64_t A = T * k;
+    const size_t es = dtype == CRAFT_BF16 ? 2 : 4;
+    const int64_t worst = T * std::min<int64_t>(k, nslots);
+    L.max_rows = max_rows_arg > 0 ? std::min(max_rows_arg, worst) : worst;
+    L.NB = (T + kTokPerBlock - 1) / kTokPerBlock;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = round_up(off + bytes, 256); return o; };
+    L.ctrl = take(CTRL_WORDS * 4);
+    L.ids = take((size_t)A * 4);
+    L.w = take((size_t)A * 4);
+    L.lrank = take((size_t)A);
+    L.dest = take((size_t)A * 4);
+    L.src = take((size_t)A * 4);
+    L.hist = take((size_t)L.NB * E * 4);
+    L.counts = take((size_t)E * 4);
+    L.slot_cnt = take((size_t)S * 4);
+    L.slot_off = take((size_t)(S + 1) * 4);
+    L.mt_start = take((size_t)(nslots + 1) * 4);
+    L.act = take((size_t)L.max_rows * I * es);
+    L.y = take((size_t)L.max_rows * H * es);
+    L.total = off;
+    return L;
+}
+
+// ---- kernel timing ---------------------------------------------------------------------
+struct Timing {
+    std::mutex mu;
+    int level = 0;
+    std::vector<hipEvent_t> ev;      // pairs
+    std::vector<int> kind;           // kernel id of each recorded pair
+    size_t used = 0;                 // pairs recorded since the last read
+} g_timing;
+
+struct ScopedEvent {
+    hipStream_t s;
+    hipEvent_t stop = nullptr;
+    ScopedEvent(int kernel, hipStream_t stream) : s(stream) {
+        Timing &t = g_timing;
+        if (t.level == 0 || (t.level == 1 && kernel != CRAFT_K_GATEUP)) return;
+        std::lock_guard<std::mutex> lk(t.mu);
+        if ((t.used + 1) * 2 > t.ev.size()) return;
+        hipEvent_t start = t.ev[t.used * 2];
+        stop = t.ev[t.used * 2 + 1];
+        t.kind[t.used] = kernel;
+        t.used += 1;
+        (void)hipEventRecord(start, s);
+    }
+    ~ScopedEvent() {
+        if (stop) (void)hipEventRecord(stop, s);
+    }
+};
+
+int cached_num_cu() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a) {
+    if (!plan || !a || layer < 0 || layer >= plan->L || rank < 0 || rank >= plan->D) return CRAFT_EINVAL;
+    if (a->dtype != CRAFT_F32 && a->dtype != CRAFT_BF16) return CRAFT_EINVAL;
+    if (a->T < 0 || a->H <= 0 || a->I <= 0 || a->k <= 0 || a->k > 64 || a->k > plan->E) return CRAFT_EINVAL;
+    if (plan->E > 1024 || a->max_rows < 0) return CRAFT_EINVAL;
+    if (a->T * (int64_t)a->k >= ((int64_t)1 << 31)) return CRAFT_EINVAL;
+    const int unit = a->dtype == CRAFT_BF16 ? 8 : 4;
+    if (a->H % unit || a->I % unit) return CRAFT_EINVAL;
+    const craft_layer_plan &lp = plan->layers[layer];
+    const int32_t nslots = lp.rank_slot_off[rank + 1] - lp.rank_slot_off[rank];
+    if (nslots > 1024) return CRAFT_EINVAL;
+    return CRAFT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t k,
+                              int32_t renormalize, int32_t *ids, float *w, void *stream) {
+    if (T < 0 || E <= 0 || E > 1024 || k <= 0 || k > E || k > 64) return CRAFT_EINVAL;
+    if (T == 0) return CRAFT_OK;
+    if (!logits || !ids || !w) return CRAFT_EINVAL;
+    RouteArgs ra{logits, T, E, k, renormalize ? 1 : 0, ids, w, nullptr, nullptr, nullptr};
+    return launch_route(ra, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
+}
+
+craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, int32_t k, int32_t E,
+                               int64_t batch_tokens, int64_t *counts, void *stream) {
+    if (L <= 0 || T < 0 || k <= 0 || E <= 0 || E > 4096 || batch_tokens <= 0) return CRAFT_EINVAL;
+    if (T == 0) return CRAFT_OK;
+    if (!topk_ids || !counts || !aligned(topk_ids, 16) || !aligned(counts, 8)) return CRAFT_EINVAL;
+    LoadArgs la{topk_ids, L, k, E, T, batch_tokens, (T + batch_tokens - 1) / batch_tokens, counts};
+    return launch_expert_load(la, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
+}
+
+craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,
+                                      void *dev_tables, size_t bytes, void *stream) {
+    if (!plan || !dev_tables || layer < 0 || layer >= plan->L || rank < 0 || rank >= plan->D)
+        return CRAFT_EINVAL;
+    if (!aligned(dev_tables, 256)) return CRAFT_EINVAL;
+    const craft_layer_plan &lp = plan->layers[layer];
+    const size_t words = craft_tables_words(plan->E, (int32_t)lp.slot_expert.size());
+    if (bytes < words * sizeof(int32_t)) return CRAFT_EWORKSPACE;
+    std::vector<int32_t> host(words);
+    craft_tables_build(lp, plan->E, rank, host.data());
+    // the staging vector dies with this call, so the copy has to be complete on return
+    if (hipMemcpyAsync(dev_tables, host.data(), words * sizeof(int32_t), hipMemcpyHostToDevice,
+                       as_stream(stream)) != hipSuccess)
+        return CRAFT_EHIP;
+    if (hipStreamSynchronize(as_stream(stream)) != hipSuccess) return CRAFT_EHIP;
+    std::lock_guard<std::mutex> lk(plan->reg_mutex);
+    for (auto &r : plan->regs)
+        if (r.dev == dev_tables) { r.layer = layer; r.rank = rank; return CRAFT_OK; }
+    plan->regs.push_back({dev_tables, layer, rank});
+    return CRAFT_OK;
+}
+
+craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                              const craft_fwd_args *a, size_t *bytes) {
+    if (!bytes) return CRAFT_EINVAL;
+    craft_status st = check_fwd(plan, layer, rank, a);
+    if (st != CRAFT_OK) return st;
+    const craft_layer_plan &lp = plan->layers[layer];
+    const int32_t nslots = lp.rank_slot_off[rank + 1] - lp.rank_slot_off[rank];
+    Layout L = make_layout(a->T, a->k, plan->E, (int32_t)lp.slot_expert.size(), nslots, a->H, a->I,
+                           a->dtype, a->max_rows);
+    *bytes = L.total;
+    return CRAFT_OK;
+}
+
+craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                    const craft_fwd_args *a, void *stream) {
+    craft_status st = check_fwd(plan, layer, rank, a);
+    if (st != CRAFT_OK) return st;
+    if (!a->workspace || !aligned(a->workspace, 256) || !a->tables) return CRAFT_EINVAL;
+    {
+        craft_plan_t *p = const_cast<craft_plan_t *>(plan);
+        std::lock_guard<std::mutex> lk(p->reg_mutex);
+        bool known = false;
+        for (auto &r : p->regs)
+            known = known || (r.dev == a->tables && r.layer == layer && r.rank == rank);
+        if (!known) return CRAFT_EINVAL;
+    }
+    const craft_layer_plan &lp = plan->layers[layer];
+    const int32_t E = plan->E, S = (int32_t)lp.slot_expert.size();
+    const int32_t s_lo = lp.rank_slot_off[rank], s_hi = lp.rank_slot_off[rank + 1];
+    const int32_t nslots = s_hi - s_lo;
+    Layout L = make_layout(a->T, a->k, E, S, nslots, a->H, a->I, a->dtype, a->max_rows);
+    if (a->workspace_bytes < L.total) return CRAFT_EWORKSPACE;
+    if (a->T > 0) {
+        if (!a->x || !a->logits || !a->out) return CRAFT_EINVAL;
+        if (!aligned(a->x, 16) || !aligned(a->out, 16) || !aligned(a->logits, 4)) return CRAFT_EINVAL;
+        if (nslots > 0 && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
+    }
+    hipStream_t s = as_stream(stream);
+    unsigned char *ws = static_cast<unsigned char *>(a->workspace);
+    int32_t *ctrl = reinterpret_cast<int32_t *>(ws + L.ctrl);
+    int32_t *ids = reinterpret_cast<int32_t *>(ws + L.ids);
+    float *w = reinterpret_cast<float *>(ws + L.w);
+    uint8_t *lrank = ws + L.lrank;
+    int32_t *dest = reinterpret_cast<int32_t *>(ws + L.dest);
+    int32_t *src = reinterpret_cast<int32_t *>(ws + L.src);
+    int32_t *hist = reinterpret_cast<int32_t *>(ws + L.hist);
+    int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
+    int32_t *slot_cnt = reinterpret_cast<int32_t *>(ws + L.slot_cnt);
+    int32_t *slot_off = reinterpret_cast<int32_t *>(ws + L.slot_off);
+    int32_t *mt_start = reinterpret_cast<int32_t *>(ws + L.mt_start);
+    const int32_t *tables = static_cast<const int32_t *>(a->tables);
+
+    // 1 route (+ per-block ranks and counts); user copies of ids / weights are written by the
+    // same kernel when asked for, so route straight into them and alias the workspace views
+    int32_t *ids_out = a->ids ? a->ids : ids;
+    float *w_out = a->topk_w ? a->topk_w : w;
+    {
+        ScopedEvent ev(CRAFT_K_ROUTE, s);
+        RouteArgs ra{a->logits, a->T, E, a->k, a->renormalize ? 1 : 0, ids_out, w_out, lrank, hist, ctrl};
+        if (launch_route(ra, s) != hipSuccess) return CRAFT_EHIP;
+    }
+    // 2 per-expert totals, slot offsets, tile table
+    {
+        ScopedEvent ev(CRAFT_K_SCAN, s);
+        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi,
+                    a->dtype == CRAFT_BF16 ? kBM_bf16 : kBM_f32, L.max_rows,
+                    counts, slot_cnt, slot_off, mt_start, ctrl,
+                    a->counts, a->slot_cnt, a->slot_off};
+        if (launch_scan(sa, s) != hipSuccess) return CRAFT_EHIP;
+    }
+    // 3 dispatch permutation
+    {
+        ScopedEvent ev(CRAFT_K_DISPATCH, s);
+        DispatchArgs da{ids_out, lrank, hist, a->T, a->k, E, tables, slot_off, dest, src, a->dest, a->src};
+        if (launch_dispatch(da, s) != hipSuccess) return CRAFT_EHIP;
+    }
+    // 4 grouped FFN
+    FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, ctrl,
+               a->w_gate, a->w_up, a->w_down, ws + L.act, ws + L.y, L.max_rows, cached_num_cu()};
+    if (a->T > 0) {
+        {
+            ScopedEvent ev(CRAFT_K_GATEUP, s);
+            if (launch_gateup(fa, s) != hipSuccess) return CRAFT_EHIP;
+        }
+        {
+            ScopedEvent ev(CRAFT_K_DOWN, s);
+            if (launch_down(fa, s) != hipSuccess) return CRAFT_EHIP;
+        }
+    }
+    // 5 combine
+    {
+        ScopedEvent ev(CRAFT_K_COMBINE, s);
+        CombineArgs ca{a->dtype, a->T, a->k, a->H, ws + L.y, dest, w_out, slot_off, s_lo, s_hi, ctrl, a->out};
+        if (launch_combine(ca, s) != hipSuccess) return CRAFT_EHIP;
+    }
+    return CRAFT_OK;
+}
+
+craft_status craft_moe_rank_forward_result(const void *workspace, int64_t *rows, int32_t *overflow) {
+    if (!workspace) return CRAFT_EINVAL;
+    int32_t ctrl[4];
+    if (hipMemcpy(ctrl, workspace, sizeof(ctrl), hipMemcpyDeviceToHost) != hipSuccess) return CRAFT_EHIP;
+    if (rows) *rows = ctrl[CTRL_ROWS];
+    if (overflow) *overflow = ctrl[CTRL_OVERFLOW];
+    return CRAFT_OK;
+}
+
+craft_status craft_timing_enable(int32_t level, int32_t max_forwards) {
+    if (level < 0 || level > 2 || max_forwards < 0) return CRAFT_EINVAL;
+    Timing &t = g_timing;
+    std::lock_guard<std::mutex> lk(t.mu);
+    const size_t pairs = level == 0 ? 0 : (size_t)max_forwards * (level == 1 ? 1 : CRAFT_K_COUNT);
+    while (t.ev.size() < pairs * 2) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return CRAFT_EHIP;
+        t.ev.push_back(e);
+    }
+    t.kind.assign(t.ev.size() / 2, 0);
+    t.used = 0;
+    t.level = level;
+    return CRAFT_OK;
+}
+
+craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_K_COUNT]) {
+    if (!ms || !launches) return CRAFT_EINVAL;
+    Timing &t = g_timing;
+    std::lock_guard<std::mutex> lk(t.mu);
+    for (int i = 0; i < CRAFT_K_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+    for (size_t i = 0; i < t.used; ++i) {
+        if (hipEventSynchronize(t.ev[2 * i + 1]) != hipSuccess) return CRAFT_EHIP;
+        float d = 0.0f;
+        if (hipEventElapsedTime(&d, t.ev[2 * i], t.ev[2 * i + 1]) != hipSuccess) return CRAFT_EHIP;
+        ms[t.kind[i]] += d;
+        launches[t.kind[i]] += 1;
+    }
+    t.used = 0;
+    return CRAFT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Internal launcher interface between the host API (forward.cpp) and the HIP kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "plan_internal.h"
+
+namespace craft {
+
+// Tokens handled by one workgroup of the routing and dispatch kernels.  Ranks of
+// assignments inside a block are taken from a 32-bit token mask per expert.
+constexpr int kTokPerBlock = 32;
+
+// Control words at the start of the workspace.
+enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3, CTRL_WORDS = 16 };
+
+// Rows per row-tile of the grouped GEMMs (the unit the tile table counts in).
+constexpr int kBM_bf16 = 128;
+constexpr int kBM_f32 = 32;
+
+struct RouteArgs {
+    const float *logits;
+    int64_t T;
+    int32_t E, k, renorm;
+    int32_t *ids;       // [T][k]
+    float *w;           // [T][k]
+    uint8_t *lrank;     // [T][k] rank of the assignment among same-expert ones of its block; may be null
+    int32_t *hist;      // [NB][E] per-block expert counts; may be null
+    int32_t *ctrl;      // control words to clear; may be null
+};
+hipError_t launch_route(const RouteArgs &a, hipStream_t s);
+
+struct ScanArgs {
+    int32_t *hist;            // [NB][E] in: counts per block; out: exclusive prefix over blocks
+    int32_t NB, E;
+    const int32_t *tables;    // device tables of this (layer, rank)
+    int32_t S, s_lo, s_hi;
+    int32_t bm;               // rows per row-tile
+    int64_t max_rows;
+    int32_t *counts;          // [E]
+    int32_t *slot_cnt;        // [S]
+    int32_t *slot_off;        // [S+1]
+    int32_t *mt_start;        // [s_hi - s_lo + 1]
+    int32_t *ctrl;
+    int32_t *user_counts, *user_slot_cnt, *user_slot_off;   // optional copies
+};
+hipError_t launch_scan(const ScanArgs &a, hipStream_t s);
+
+struct DispatchArgs {
+    const int32_t *ids;
+    const uint8_t *lrank;
+    const int32_t *base;      // [NB][E]
+    int64_t T;
+    int32_t k, E;
+    const int32_t *tables;
+    const int32_t *slot_off;
+    int32_t *dest, *src;
+    int32_t *user_dest, *user_src;
+};
+hipError_t launch_dispatch(const DispatchArgs &a, hipStream_t s);
+
+struct FfnArgs {
+    int32_t dtype;
+    int32_t H, I, k;
+    int32_t s_lo, nslots;
+    const void *x;                 // [T][H]
+    const int32_t *src;            // [A]
+    const int32_t *slot_off;       // [S+1]
+    const int32_t *mt_start;       // [nslots+1]
+    const int32_t *ctrl;
+    const void *const *w_gate, *const *w_up, *const *w_down;
+    void *act;                     // [max_rows][I] SwiGLU activations
+    void *y;                       // [max_rows][H]
+    int64_t max_rows;
+    int32_t num_cu;
+};
+hipError_t launch_gateup(const FfnArgs &a, hipStream_t s);
+hipError_t launch_down(const FfnArgs &a, hipStream_t s);
+
+struct CombineArgs {
+    int32_t dtype;
+    int64_t T;
+    int32_t k, H;
+    const void *y;
+    const int32_t *dest;
+    const float *w;
+    const int32_t *slot_off;
+    int32_t s_lo, s_hi;
+    const int32_t *ctrl;
+    void *out;
+};
+hipError_t launch_combine(const CombineArgs &a, hipStream_t s);
+
+struct LoadArgs {
+    const int32_t *ids;       // [L][T][k]
+    int32_t L, k, E;
+    int64_t T, batch_tokens, B;
+    int64_t *counts;          // [B][L][E]
+};
+hipError_t launch_expert_load(const LoadArgs &a, hipStream_t s);
+
+}  // namespace craft

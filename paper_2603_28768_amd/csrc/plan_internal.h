@@ -1,0 +1,50 @@
+// Internal layout of the plan object and of the per-rank device tables.
+#pragma once
+
+#include <cstdint>
+#include <mutex>
+#include <vector>
+
+#include "craft.h"
+
+struct craft_layer_plan {
+    int32_t n_replicas = 0;
+    std::vector<int32_t> copies;         // [E]
+    std::vector<int32_t> slot_expert;    // [S]
+    std::vector<int32_t> rank_slot_off;  // [D+1]
+    std::vector<int64_t> rank_load;      // [D]
+    int64_t est_max_rank_load = 0;
+    double est_balancedness = 1.0;
+};
+
+struct craft_table_reg {
+    const void *dev;
+    int32_t layer, rank;
+};
+
+struct craft_plan {
+    int32_t L = 0, E = 0, D = 0, gpus_per_node = 0;
+    std::vector<craft_layer_plan> layers;
+    std::vector<int32_t> order;          // objective 0: layer that received each replica
+    std::mutex reg_mutex;
+    std::vector<craft_table_reg> regs;   // device table buffers filled from this plan
+};
+
+// Device tables of one (layer, rank): a header followed by int32 arrays, all offsets in
+// int32 units from the start of the buffer.
+//   copies      [E]    copies of expert e
+//   efirst      [E+1]  eslots[efirst[e] + q] = slot holding copy q of expert e
+//   eslots      [S]
+//   slot_expert [S]
+//   slot_copy   [S]    which copy of its expert the slot is
+struct craft_tables_header {
+    uint32_t magic;
+    int32_t E, S, s_lo, s_hi;
+    int32_t off_copies, off_efirst, off_eslots, off_slot_expert, off_slot_copy;
+    int32_t total_words;
+    int32_t pad;
+};
+static const uint32_t CRAFT_TABLES_MAGIC = 0x43524146u;
+
+size_t craft_tables_words(int32_t E, int32_t S);
+void craft_tables_build(const craft_layer_plan &lp, int32_t E, int32_t rank, int32_t *buf);

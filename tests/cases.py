@@ -1,0 +1,65 @@
+"""Builds one synthetic case end to end on the CPU checker side (profiling loads, plan,
+evaluation batch, heaviest rank) for the GPU parity tests.  The plan comes from the
+library's host planner and is asserted equal to the checker's."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from oracle import plan_oracle as po
+from paper_2603_28768_amd import binding, synth
+
+
+class Case:
+    def __init__(self, cfg: synth.LayerConfig, rank=None):
+        self.cfg = cfg
+        self.pop = synth.layer_popularity(cfg)
+        W = np.zeros((cfg.profile_batches, 1, cfg.E), dtype=np.int64)
+        for b in range(cfg.profile_batches):
+            ids, _ = oracle.route(synth.router_logits(cfg, self.pop, "profile", b), cfg.k)
+            W[b, 0] = oracle.expert_load(ids[None], cfg.E, max(cfg.T, 1))[0, 0]
+        self.W = W
+        self.plan = binding.Plan(W, cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
+        ref = po.make_plan(W.tolist(), cfg.D, None, cfg.replica_slots)
+        self.layer = self.plan.layer(0)
+        assert self.layer["slot_expert"].tolist() == ref["layers"][0]["slot_expert"]
+        assert self.layer["rank_slot_off"].tolist() == ref["layers"][0]["rank_slot_off"]
+        self.slot_expert = self.layer["slot_expert"]
+        self.rank_slot_off = self.layer["rank_slot_off"]
+        self.logits = synth.router_logits(cfg, self.pop, "eval")
+        self.x = synth.activations(cfg)
+        self.ids, self.w = oracle.route(self.logits, cfg.k)
+        self.dest, self.src, self.slot_cnt, self.slot_off = oracle.dispatch(
+            self.ids, cfg.E, self.slot_expert)
+        self.rows = po.realized_rank_rows(self.slot_cnt.tolist(), self.rank_slot_off.tolist())
+        self.heaviest = po.heaviest_rank(self.rows)
+        self._wcache = {}
+
+    def weights_of(self, e: int):
+        if e not in self._wcache:
+            self._wcache[e] = synth.expert_weights(self.cfg, e)
+        return self._wcache[e]
+
+    def rank_slots(self, rank: int):
+        return [int(e) for e in self.slot_expert[self.rank_slot_off[rank]:self.rank_slot_off[rank + 1]]]
+
+    def oracle_rank(self, rank: int, tokens=None) -> dict:
+        return oracle.rank_forward(self.x, self.logits, self.cfg.k, self.slot_expert,
+                                   self.rank_slot_off, rank, self.weights_of, True, tokens)
+
+    def gpu_rank(self, rank: int, max_rows: int = 0, debug: bool = True, device="cuda:0"):
+        """(RankForward, x_dev, logits_dev) with this rank's weights resident."""
+        import torch
+        cfg = self.cfg
+        wg, wu, wd = [], [], []
+        dev_cache = {}
+        for e in self.rank_slots(rank):
+            if e not in dev_cache:
+                dev_cache[e] = tuple(binding.to_device(m, cfg.dtype, device) for m in self.weights_of(e))
+            g, u, d = dev_cache[e]
+            wg.append(g); wu.append(u); wd.append(d)
+        fwd = binding.RankForward(self.plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
+                                  wg, wu, wd, True, max_rows, device, want_debug_outputs=debug)
+        x = binding.to_device(self.x, cfg.dtype, device)
+        logits = torch.from_numpy(self.logits).to(device)
+        return fwd, x, logits

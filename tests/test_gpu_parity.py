@@ -1,0 +1,243 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU checker on the same
+seeded inputs.  Integer results (ids, counts, dispatch indices) are compared bit for bit;
+gate weights to 1e-5 relative; the layer output to max|gpu-ref| <= tol * max|ref| with
+tol = 1e-2 for bf16 storage (fp32 accumulation) and 1e-4 for fp32 storage."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_28768_amd import binding, synth
+
+from cases import Case
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 1e-2, "f32": 1e-4}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    assert os.path.exists(binding.LIB_PATH), "libcraft.so has not been built"
+    binding.lib()
+    return torch
+
+
+def _np(t):
+    return t.detach().float().cpu().numpy() if t.dtype.is_floating_point else t.detach().cpu().numpy()
+
+
+# ----------------------------------------------------------------------- route
+
+@pytest.mark.parametrize("T,E,k,quantum,renorm", [
+    (256, 16, 2, None, True), (1000, 128, 8, None, True), (333, 256, 8, None, False),
+    (97, 384, 8, None, True), (64, 100, 5, 0.5, True), (40, 7, 7, 1.0, False),
+    (33, 1, 1, None, True), (31, 1000, 64, 0.25, True), (4096, 128, 8, None, True)])
+def test_route_parity(torch_cuda, T, E, k, quantum, renorm):
+    torch = torch_cuda
+    print(f"route T={T} E={E} k={k} quantum={quantum} renorm={renorm}", flush=True)
+    g = np.random.default_rng(T * 131 + E)
+    l = (g.standard_normal((T, E)) * 2).astype(np.float32)
+    if quantum:
+        l = (np.round(l / quantum) * quantum).astype(np.float32)      # many exact ties
+    ids, w = binding.route_topk(torch.from_numpy(l).cuda(), k, renorm)
+    torch.cuda.synchronize()
+    rid, rw = oracle.route(l, k, renorm)
+    assert np.array_equal(_np(ids), rid)
+    assert np.allclose(_np(w), rw, rtol=1e-5, atol=1e-30)
+
+
+# ------------------------------------------------------------------------ load
+
+@pytest.mark.parametrize("L,T,k,E,bt", [
+    (1, 256, 2, 16, 256), (3, 1000, 8, 128, 256), (2, 17, 3, 9, 5), (2, 9000, 8, 256, 4500),
+    (1, 20000, 8, 384, 20000), (4, 4096, 8, 4096, 1024), (1, 7, 1, 1, 2)])
+def test_expert_load_parity(torch_cuda, L, T, k, E, bt):
+    torch = torch_cuda
+    print(f"load L={L} T={T} k={k} E={E} bt={bt}", flush=True)
+    g = np.random.default_rng(L * 7 + T)
+    pop = synth.popularity(E, 1.3, 0)
+    ids = g.choice(E, size=(L, T, k), p=pop).astype(np.int32)
+    got = binding.expert_load(torch.from_numpy(ids).cuda(), E, bt)
+    torch.cuda.synchronize()
+    want = oracle.expert_load(ids, E, bt)
+    assert np.array_equal(_np(got), want)
+
+
+def test_expert_load_on_a_zipf_trace(torch_cuda):
+    # the multi-layer stack's trace shape at reduced length: 58 layers x 256 experts, top-8
+    torch = torch_cuda
+    L, E, k, T, bt = 58, 256, 8, 8192, 4096
+    s = synth.trace_layer_exponents(L, 5)
+    ids = np.stack([synth.routing_trace_layer(E, k, T, s[l], 5, l) for l in range(L)])
+    print("zipf trace", ids.shape, flush=True)
+    got = _np(binding.expert_load(torch.from_numpy(ids).cuda(), E, bt))
+    torch.cuda.synchronize()
+    want = oracle.expert_load(ids, E, bt)
+    assert np.array_equal(got, want)
+    assert np.all(got.sum(-1) == bt * k)
+
+
+# --------------------------------------------------------------------- forward
+
+def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0):
+    cfg = case.cfg
+    fwd, x, logits = case.gpu_rank(rank, max_rows)
+    out = fwd(x, logits)
+    rows, ovf = fwd.result()
+    ref = case.oracle_rank(rank, tokens)
+    d = {k: _np(v) for k, v in fwd.debug.items()}
+    assert np.array_equal(d["ids"], ref["ids"])
+    assert np.allclose(d["topk_w"], ref["w"], rtol=1e-5, atol=1e-30)
+    assert np.array_equal(d["counts"], ref["counts"])
+    assert np.array_equal(d["slot_cnt"], ref["slot_cnt"])
+    assert np.array_equal(d["slot_off"], ref["slot_off"])
+    assert np.array_equal(d["dest"].reshape(-1), ref["dest"])
+    assert np.array_equal(d["src"], ref["src"])
+    assert rows == ref["rows"] and ovf == 0
+    got = _np(out).astype(np.float64)
+    if tokens is not None:
+        got = got[np.asarray(tokens)]
+    scale = np.abs(ref["out"]).max()
+    err = np.abs(got - ref["out"]).max()
+    print(f"  rank {rank}: rows={rows} max|ref|={scale:.4g} max|err|={err:.3g} "
+          f"rel={err / max(scale, 1e-30):.3g}", flush=True)
+    assert err <= TOL[cfg.dtype] * scale + 1e-30
+    return _np(out).astype(np.float64), ref
+
+
+def test_tiny_layer_all_ranks(torch_cuda):
+    # the tiny fp32 layer: every rank's share executes; their sum is the un-sharded layer
+    case = Case(synth.CONFIGS["tiny"])
+    cfg = case.cfg
+    print("tiny", case.rows, flush=True)
+    total = np.zeros((cfg.T, cfg.H))
+    ref_total = np.zeros((cfg.T, cfg.H))
+    for g in range(cfg.D):
+        out, ref = _check_rank(torch_cuda, case, g)
+        total += out
+        ref_total += ref["out"]
+    assert np.abs(total - ref_total).max() <= TOL["f32"] * np.abs(ref_total).max()
+
+
+@pytest.mark.parametrize("dtype,T,H,I,E,k,D,slots", [
+    ("bf16", 600, 512, 384, 32, 4, 4, 4),        # several row tiles, ragged last tile
+    ("bf16", 517, 520, 200, 24, 8, 3, 5),        # ragged K (520, 200) and ragged N (200)
+    ("bf16", 96, 256, 128, 8, 2, 8, 0),          # one expert per rank, no replicas
+    ("f32", 300, 100, 60, 12, 3, 2, 3),          # fp32 path with ragged everything
+    ("bf16", 1500, 256, 192, 16, 8, 1, 0),       # single rank holds everything
+    ("bf16", 40, 128, 64, 6, 1, 2, 2)])          # top-1
+def test_reduced_layers_every_rank(torch_cuda, dtype, T, H, I, E, k, D, slots):
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], dtype=dtype, T=T, H=H, I=I, E=E, k=k, D=D,
+                       replica_slots=slots, zipf_s=1.2, profile_batches=2)
+    print("reduced", cfg, flush=True)
+    case = Case(cfg)
+    for g in range(D):
+        _check_rank(torch_cuda, case, g)
+
+
+def test_forward_is_reproducible_bit_for_bit(torch_cuda):
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=700, H=256, I=256, E=32, D=4, replica_slots=4,
+                       profile_batches=2)
+    case = Case(cfg)
+    fwd, x, logits = case.gpu_rank(case.heaviest)
+    a = fwd(x, logits).clone()
+    da = {k: v.clone() for k, v in fwd.debug.items()}
+    for _ in range(3):
+        b = fwd(x, logits)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        for k, v in fwd.debug.items():
+            assert torch.equal(da[k], v), k
+
+
+def test_rank_without_rows_and_unused_experts(torch_cuda):
+    # strong skew on few tokens: some experts (and with D = E some ranks) get nothing
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=24, H=128, I=64, E=16, k=2, D=16,
+                       replica_slots=0, zipf_s=3.0, profile_batches=1)
+    case = Case(cfg)
+    assert min(case.rows) == 0
+    for g in (int(np.argmin(case.rows)), case.heaviest):
+        out, _ = _check_rank(torch_cuda, case, g)
+        if case.rows[g] == 0:
+            assert np.all(out == 0)
+
+
+def test_empty_batch(torch_cuda):
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=0)
+    W = np.ones((1, 1, cfg.E), dtype=np.int64)
+    plan = binding.Plan(W, cfg.D, 0)
+    ws = [torch.zeros((cfg.I, cfg.H), device="cuda") for _ in range(4)]
+    wd = [torch.zeros((cfg.H, cfg.I), device="cuda") for _ in range(4)]
+    fwd = binding.RankForward(plan, 0, 0, "f32", 0, cfg.H, cfg.I, cfg.k, ws, ws, wd)
+    out = fwd(torch.empty((0, cfg.H), device="cuda"), torch.empty((0, cfg.E), device="cuda"))
+    rows, ovf = fwd.result()
+    assert tuple(out.shape) == (0, cfg.H) and rows == 0 and ovf == 0
+
+
+def test_overflow_is_reported_not_computed(torch_cuda):
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=256, H=128, I=64, E=8, k=2, D=2,
+                       replica_slots=0, profile_batches=1)
+    case = Case(cfg)
+    g = case.heaviest
+    fwd, x, logits = case.gpu_rank(g, max_rows=case.rows[g] - 1)
+    out = fwd(x, logits)
+    rows, ovf = fwd.result()
+    assert rows == case.rows[g] and ovf == 1
+    assert np.all(_np(out) == 0)
+    fwd2, x, logits = case.gpu_rank(g, max_rows=case.rows[g])      # exactly enough
+    fwd2(x, logits)
+    assert fwd2.result() == (case.rows[g], 0)
+
+
+def test_forward_rejects_foreign_tables(torch_cuda):
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["tiny"], T=64)
+    case = Case(cfg)
+    fwd, x, logits = case.gpu_rank(0)
+    other = case.plan.upload_tables(0, 1)
+    fwd.args.tables = other.data_ptr()                              # tables of another rank
+    with pytest.raises(binding.CraftError):
+        fwd(x, logits)
+    fwd.args.tables = x.data_ptr()                                  # not a table buffer at all
+    with pytest.raises(binding.CraftError):
+        fwd(x, logits)
+
+
+# -------------------------------------------------- full-size configurations
+
+def _sampled_tokens(case: Case, rank: int, n: int):
+    """Tokens that have at least one row on the rank (plus a few that have none)."""
+    cfg = case.cfg
+    lo = int(case.slot_off[case.rank_slot_off[rank]])
+    hi = int(case.slot_off[case.rank_slot_off[rank + 1]])
+    d = case.dest.reshape(cfg.T, cfg.k)
+    on = np.nonzero(((d >= lo) & (d < hi)).any(1))[0]
+    off = np.nonzero(~((d >= lo) & (d < hi)).any(1))[0]
+    g = np.random.default_rng(1)
+    pick = list(g.choice(on, size=min(n, on.size), replace=False))
+    pick += list(off[:2])
+    # make sure the last row of the rank (ragged tail of the last tile) is covered
+    pick.append(int(case.src[hi - 1] // cfg.k))
+    return sorted(set(int(t) for t in pick))
+
+
+@pytest.mark.parametrize("name", ["qwen3", "dsv3", "kimi"])
+def test_full_size_heaviest_rank_sampled(torch_cuda, name):
+    # the launch configuration the benchmark times: full shapes, the heaviest rank's share;
+    # integer results checked everywhere, the output on sampled tokens the checker can afford
+    cfg = synth.CONFIGS[name]
+    print("full size", cfg, flush=True)
+    case = Case(cfg)
+    g = case.heaviest
+    print(f"  rows per rank: max={max(case.rows)} mean={np.mean(case.rows):.0f} heaviest={g} "
+          f"slots={case.rank_slots(g)}", flush=True)
+    toks = _sampled_tokens(case, g, 12)
+    _check_rank(torch_cuda, case, g, tokens=toks)
