@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Throughput of one expert-parallel rank's MoE layer under a CRAFT replication plan.
+
+A step is one craft_moe_rank_forward call (route, load counts, replica-aware dispatch,
+grouped SwiGLU FFN, combine) on the heaviest simulated rank of the workload, inputs and
+weights resident in HBM.  The plan is made once before the timed region, through the
+library (GPU routing of the profiling batches -> craft_expert_load -> craft_plan), as the
+paper does at initialisation (Sec. 5.4: planning has no inference-time cost).
+
+Prints one JSON line: tokens/s of the layer, plus
+  roofline      for the dominant kernel (grouped gate/up GEMM): algorithmic bytes and flops
+                per launch over its HIP-event duration measured inside the timed region
+  cpu_baseline  the CPU checker timed on this host on a bounded sample of the same rank
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def setup(cfg, dev="cuda:0"):
+    """Profiling -> plan -> evaluation batch -> heaviest rank, all through the library."""
+    import torch
+    from paper_2603_28768_amd import binding, synth
+
+    pop = synth.layer_popularity(cfg)
+    prof = np.concatenate([synth.router_logits(cfg, pop, "profile", b)
+                           for b in range(cfg.profile_batches)])
+    ids, _ = binding.route_topk(torch.from_numpy(prof).to(dev), cfg.k)
+    W = binding.expert_load(ids.reshape(1, -1, cfg.k), cfg.E, cfg.T)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plan = binding.Plan(W.cpu().numpy(), cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+
+    logits = synth.router_logits(cfg, pop, "eval")
+    x = synth.activations(cfg)
+    d_logits = torch.from_numpy(logits).to(dev)
+    eids, _ = binding.route_topk(d_logits, cfg.k)
+    counts = binding.expert_load(eids.reshape(1, -1, cfg.k), cfg.E, cfg.T)[0, 0].cpu().numpy()
+    rows, rank = plan.rank_rows(0, counts)
+    lay = plan.layer(0)
+    slots = [int(e) for e in lay["slot_expert"][lay["rank_slot_off"][rank]:lay["rank_slot_off"][rank + 1]]]
+    host_w, dev_w = {}, {}
+    for e in slots:
+        if e not in host_w:
+            host_w[e] = synth.expert_weights(cfg, e)
+            dev_w[e] = tuple(binding.to_device(m, cfg.dtype, dev) for m in host_w[e])
+    fwd = binding.RankForward(plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
+                              [dev_w[e][0] for e in slots], [dev_w[e][1] for e in slots],
+                              [dev_w[e][2] for e in slots])
+    d_x = binding.to_device(x, cfg.dtype, dev)
+    # rows per local slot (for the algorithmic byte count): copy q of expert e gets the
+    # tokens i < n with i mod c == q
+    seen, slot_rows = {}, []
+    for p, e in enumerate(lay["slot_expert"]):
+        q = seen.get(int(e), 0)
+        seen[int(e)] = q + 1
+        n, c = int(counts[e]), int(lay["copies"][e])
+        if lay["rank_slot_off"][rank] <= p < lay["rank_slot_off"][rank + 1]:
+            slot_rows.append((n - q + c - 1) // c if n > q else 0)
+    return dict(plan=plan, plan_ms=plan_ms, lay=lay, rank=rank, rows=rows, slots=slots,
+                slot_rows=slot_rows, fwd=fwd, x=d_x, logits=d_logits, host_x=x,
+                host_logits=logits, host_w=host_w)
+
+
+def cpu_baseline(cfg, st, budget_s=15.0):
+    """The CPU checker on this host: routing, dispatch and combine on the whole batch, the
+    FFN on a sample of the rank's rows sized to about `budget_s` seconds, scaled to all rows."""
+    import oracle
+    lay, rank, k = st["lay"], st["rank"], cfg.k
+    t = time.perf_counter()
+    ids, w = oracle.route(st["host_logits"], k)
+    t_route = time.perf_counter() - t
+    t = time.perf_counter()
+    dest, src, cnt, off = oracle.dispatch(ids, cfg.E, lay["slot_expert"])
+    t_disp = time.perf_counter() - t
+    p_lo, p_hi = lay["rank_slot_off"][rank], lay["rank_slot_off"][rank + 1]
+    lo, hi = int(off[p_lo]), int(off[p_hi])
+    M = hi - lo
+    x = st["host_x"]
+    threads = oracle.num_threads()
+    # calibrate on a few rows, then take an evenly spaced sample of every slot
+    p0 = next(p for p in range(p_lo, p_hi) if cnt[p] > 0)
+    Wg, Wu, Wd = st["host_w"][int(lay["slot_expert"][p0])]
+    probe = x[src[off[p0]:off[p0] + min(cnt[p0], threads)] // k]
+    t = time.perf_counter()
+    oracle.ffn_rows(probe, Wg, Wu, Wd)
+    per_row = (time.perf_counter() - t) / len(probe)
+    stride = max(1, int(np.ceil(M * per_row / budget_s)))
+    Y = np.zeros((M, cfg.H))
+    done, t_ffn = 0, 0.0
+    for p in range(p_lo, p_hi):
+        rows = np.arange(int(off[p]), int(off[p + 1]), stride)
+        if rows.size == 0:
+            continue
+        Wg, Wu, Wd = st["host_w"][int(lay["slot_expert"][p])]
+        xr = x[src[rows] // k]
+        t = time.perf_counter()
+        Y[rows - lo] = oracle.ffn_rows(xr, Wg, Wu, Wd)
+        t_ffn += time.perf_counter() - t
+        done += rows.size
+    t = time.perf_counter()
+    oracle.combine(Y, lo, dest, w, cfg.T, k)
+    t_comb = time.perf_counter() - t
+    est = t_route + t_disp + t_ffn * (M / max(done, 1)) + t_comb
+    return dict(value=cfg.T / est, unit="tokens/s", cores=threads, kind="oracle",
+                sample=f"route+dispatch+combine on all {cfg.T} tokens; FFN on every "
+                       f"{stride}-th row of each slot ({done} of {M} rows, {t_ffn:.1f} s), "
+                       f"scaled to all rows; fp64 accumulation",
+                est_seconds_per_step=est)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="qwen3", help="tiny | qwen3 | dsv3 | kimi | dsv3_long")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--timing-level", type=int, default=1,
+                    help="1: HIP events around the gate/up GEMM; 2: around every kernel")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU's share (the heaviest simulated rank); "
+            "--gpus above 1 is not part of this build")
+        sys.exit(2)
+
+    import torch
+    from paper_2603_28768_amd import binding, synth
+    binding.lib()                       # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = synth.CONFIGS[args.config]
+    st = setup(cfg)
+    fwd, x, logits = st["fwd"], st["x"], st["logits"]
+    M = int(st["rows"][st["rank"]])
+    log(f"config {cfg.name}: T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E} k={cfg.k} D={cfg.D}; "
+        f"heaviest rank {st['rank']} holds {len(st['slots'])} slots, {M} rows "
+        f"(mean {np.mean(st['rows']):.0f}); plan {st['plan_ms']:.2f} ms")
+
+    for _ in range(args.warmup):
+        fwd(x, logits)
+    torch.cuda.synchronize()
+    binding.timing_enable(args.timing_level, args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fwd(x, logits)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    times = binding.timing_read()
+    binding.timing_enable(0, 0)
+    rows, ovf = fwd.result()
+    assert ovf == 0 and rows == M, (rows, M, ovf)
+
+    ms_step = dt / args.steps * 1e3
+    es = 2 if cfg.dtype == "bf16" else 4
+    live = sum(1 for r in st["slot_rows"] if r > 0)
+    gu_ms = times["gateup"]["ms"] / max(times["gateup"]["launches"], 1)
+    gu_bytes = live * 2 * cfg.H * cfg.I * es + M * cfg.H * es + M * cfg.I * es
+    gu_flops = 4.0 * cfg.H * cfg.I * M
+    gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
+    tfs = gu_flops / (gu_ms * 1e-3) / 1e12
+    flop_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+    t_hbm, t_mfma = gu_bytes / (HBM_PEAK_GBS * 1e9), gu_flops / (flop_peak * 1e12)
+    if t_hbm >= t_mfma:
+        roof = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=gbs / HBM_PEAK_GBS, traffic=None)
+    else:
+        roof = dict(bound="mfma" if cfg.dtype == "bf16" else "alu", achieved=tfs, peak=flop_peak,
+                    unit="TFLOP/s", frac=tfs / flop_peak, traffic=None)
+    roof.update(kernel="grouped gate/up GEMM + SwiGLU", avg_ms=gu_ms,
+                launches=times["gateup"]["launches"], algorithmic_bytes=gu_bytes,
+                algorithmic_flops=gu_flops, hbm_frac=gbs / HBM_PEAK_GBS, flop_frac=tfs / flop_peak,
+                achieved_gbs=gbs, achieved_tflops=tfs)
+
+    out = dict(metric="MoE rank-forward tokens/s on 1 GPU", value=cfg.T / (ms_step * 1e-3),
+               unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=ms_step, higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype=cfg.dtype, data="synthetic",
+               config=dict(workload=f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} "
+                                    f"I={cfg.I} Zipf s={cfg.zipf_s}, {cfg.D} simulated ranks, "
+                                    f"{cfg.replica_slots} replica slots; heaviest rank's share",
+                           rank=int(st["rank"]), rank_slots=len(st["slots"]), rank_rows=M,
+                           rows_per_s=M / (ms_step * 1e-3), plan_ms=st["plan_ms"],
+                           balancedness_realized=float(np.mean(st["rows"]) / np.max(st["rows"]))),
+               roofline=roof)
+    if args.timing_level == 2:
+        out["kernel_ms"] = {k: v["ms"] / max(v["launches"], 1) for k, v in times.items()}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, st)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
