@@ -35,7 +35,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup(cfg, dev="cuda:0"):
+def setup(cfg, dev="cuda:0", packed=True):
     """Profiling -> plan -> evaluation batch -> heaviest rank, all through the library."""
     import torch
     from paper_2603_28768_amd import binding, synth
@@ -63,9 +63,13 @@ def setup(cfg, dev="cuda:0"):
         if e not in host_w:
             host_w[e] = synth.expert_weights(cfg, e)
             dev_w[e] = tuple(binding.to_device(m, cfg.dtype, dev) for m in host_w[e])
+    # model loading: weights are re-ordered once for the weight-streaming kernels
+    packed = packed and cfg.dtype == "bf16"
+    pk = {e: binding.pack_weights(*dev_w[e]) for e in dev_w} if packed else None
     fwd = binding.RankForward(plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                               [dev_w[e][0] for e in slots], [dev_w[e][1] for e in slots],
-                              [dev_w[e][2] for e in slots])
+                              [dev_w[e][2] for e in slots],
+                              packed=[pk[e] for e in slots] if packed else None)
     d_x = binding.to_device(x, cfg.dtype, dev)
     # rows per local slot (for the algorithmic byte count): copy q of expert e gets the
     # tokens i < n with i mod c == q
@@ -135,6 +139,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="qwen3", help="tiny | qwen3 | dsv3 | kimi | dsv3_long")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unpacked", action="store_true",
+                    help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
     ap.add_argument("--timing-level", type=int, default=1,
                     help="1: HIP events around the gate/up GEMM; 2: around every kernel")
     args = ap.parse_args()
@@ -148,7 +154,7 @@ def main():
     binding.lib()                       # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = synth.CONFIGS[args.config]
-    st = setup(cfg)
+    st = setup(cfg, packed=not args.unpacked)
     fwd, x, logits = st["fwd"], st["x"], st["logits"]
     M = int(st["rows"][st["rank"]])
     log(f"config {cfg.name}: T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E} k={cfg.k} D={cfg.D}; "
@@ -200,6 +206,7 @@ def main():
                                     f"{cfg.replica_slots} replica slots; heaviest rank's share",
                            rank=int(st["rank"]), rank_slots=len(st["slots"]), rank_rows=M,
                            rows_per_s=M / (ms_step * 1e-3), plan_ms=st["plan_ms"],
+                           weights="packed at load" if (not args.unpacked and cfg.dtype == "bf16") else "row-major",
                            balancedness_realized=float(np.mean(st["rows"]) / np.max(st["rows"]))),
                roofline=roof)
     if args.timing_level == 2:

@@ -142,6 +142,24 @@ craft_status craft_plan_tables_bytes(const craft_plan_t *plan, int32_t layer, in
 craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,
                                       void *dev_tables, size_t bytes, void *stream);
 
+/* --------------------------------------------------------------- weight packing
+ * One-time re-ordering of one expert's bf16 weights into the order the grouped-GEMM
+ * kernels stream them in (MFMA operand fragments: 64 lanes x 16 bytes per 32-row x
+ * 16-element block; gate and up rows of the same output columns interleaved 16 + 16;
+ * rows and contraction padded with zeros to whole blocks).  It belongs to model loading,
+ * like placing the weights in HBM, and is not part of a forward.
+ *   w_gate, w_up  DEVICE [I][H] bf16;  w_down DEVICE [H][I] bf16 (Sec. 2.1: up-projection,
+ *                 non-linearity, down-projection)
+ *   packed_gateup, packed_down  DEVICE buffers of the sizes craft_pack_weights_bytes
+ *                 returns, 16-byte aligned, written in full
+ * dtype must be CRAFT_BF16 (fp32 weights are always read row-major); H % 8 == 0, I % 8 == 0.
+ */
+craft_status craft_pack_weights_bytes(int32_t dtype, int32_t H, int32_t I, size_t *gateup_bytes,
+                                      size_t *down_bytes);
+craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void *w_gate,
+                                const void *w_up, const void *w_down, void *packed_gateup,
+                                void *packed_down, void *stream);
+
 /* ------------------------------------------------------------------- execution
  * One rank's share of one MoE layer (Sec. 2.1) under the plan:
  *   1 route       ids, w = top-k of logits                         (as craft_route_topk)
@@ -159,6 +177,10 @@ craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t
  *   w_gate, w_up  DEVICE arrays of s device pointers, one per slot of this rank in slot
  *                 order, each to a [I][H] matrix of dtype
  *   w_down        likewise, each [H][I]
+ *   w_gateup_packed, w_down_packed  DEVICE arrays of s device pointers to the buffers
+ *                 craft_pack_weights filled for each slot's expert.  When both are given
+ *                 (bf16 only) the FFN streams these and w_gate / w_up / w_down may be NULL;
+ *                 when NULL the FFN reads the row-major matrices.
  *   out      DEVICE [T][H] dtype, fully overwritten
  *   ids, topk_w, dest, src  optional DEVICE outputs [T][k] (int32/fp32/int32/int32);
  *                 NULL = kept in the workspace only
@@ -183,6 +205,8 @@ typedef struct {
     const void *const *w_gate;
     const void *const *w_up;
     const void *const *w_down;
+    const void *const *w_gateup_packed;
+    const void *const *w_down_packed;
     void *out;
     int32_t *ids;
     float *topk_w;

@@ -31,7 +31,8 @@ class PlanParams(ctypes.Structure):
 class FwdArgs(ctypes.Structure):
     _fields_ = [("dtype", c_i32), ("T", c_i64), ("H", c_i32), ("I", c_i32), ("k", c_i32),
                 ("renormalize", c_i32), ("x", c_vp), ("logits", c_vp), ("w_gate", c_vp),
-                ("w_up", c_vp), ("w_down", c_vp), ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
+                ("w_up", c_vp), ("w_down", c_vp), ("w_gateup_packed", c_vp), ("w_down_packed", c_vp),
+                ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
                 ("dest", c_vp), ("src", c_vp), ("counts", c_vp), ("slot_cnt", c_vp),
                 ("slot_off", c_vp), ("max_rows", c_i64), ("tables", c_vp), ("workspace", c_vp),
                 ("workspace_bytes", c_sz)]
@@ -52,6 +53,8 @@ EXPORTS = {
     "craft_plan_rank_rows": (ctypes.c_int, [c_vp, c_i32, c_vp, c_vp, P(c_i32)]),
     "craft_plan_tables_bytes": (ctypes.c_int, [c_vp, c_i32, c_i32, P(c_sz)]),
     "craft_plan_tables_upload": (ctypes.c_int, [c_vp, c_i32, c_i32, c_vp, c_sz, c_vp]),
+    "craft_pack_weights_bytes": (ctypes.c_int, [c_i32, c_i32, c_i32, P(c_sz), P(c_sz)]),
+    "craft_pack_weights": (ctypes.c_int, [c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp]),
     "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
     "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
@@ -215,13 +218,27 @@ def to_device(a: np.ndarray, dtype: str, device="cuda:0"):
     return t.to(device=device, dtype=_torch_dtype(dtype)).contiguous()
 
 
+def pack_weights(w_gate, w_up, w_down, stream=None):
+    """bf16 device matrices of one expert -> (packed_gateup, packed_down) device buffers."""
+    import torch
+    I, H = w_gate.shape
+    assert w_gate.dtype == torch.bfloat16 and tuple(w_up.shape) == (I, H) and tuple(w_down.shape) == (H, I)
+    a, b = c_sz(), c_sz()
+    _check(lib().craft_pack_weights_bytes(CRAFT_BF16, H, I, a, b), "craft_pack_weights_bytes")
+    pgu = torch.empty(a.value, dtype=torch.uint8, device=w_gate.device)
+    pdn = torch.empty(b.value, dtype=torch.uint8, device=w_gate.device)
+    _check(lib().craft_pack_weights(CRAFT_BF16, H, I, _dev(w_gate), _dev(w_up), _dev(w_down),
+                                    _dev(pgu), _dev(pdn), _stream_ptr(stream)), "craft_pack_weights")
+    return pgu, pdn
+
+
 class RankForward:
     """Buffers and argument block for repeated forwards of one (plan, layer, rank)."""
 
     def __init__(self, plan: Plan, layer: int, rank: int, dtype: str, T: int, H: int, I: int,
                  k: int, w_gate: Sequence, w_up: Sequence, w_down: Sequence,
                  renormalize: bool = True, max_rows: int = 0, device="cuda:0",
-                 want_debug_outputs: bool = False):
+                 want_debug_outputs: bool = False, packed: Optional[Sequence] = None):
         import torch
         self.plan, self.layer, self.rank = plan, layer, rank
         self.dtype, self.T, self.H, self.I, self.k = dtype, T, H, I, k
@@ -239,6 +256,10 @@ class RankForward:
         mk = lambda ws: torch.tensor([w.data_ptr() for w in ws] or [0], dtype=torch.int64,
                                      device=device)
         self._ptrs = (mk(w_gate), mk(w_up), mk(w_down))
+        self._packed = None
+        if packed is not None:           # list of (packed_gateup, packed_down) per slot
+            assert len(packed) == self.nslots and dtype == "bf16"
+            self._packed = (list(packed), mk([p[0] for p in packed]), mk([p[1] for p in packed]))
         self.tables = plan.upload_tables(layer, rank, device)
         self.out = torch.empty((T, H), dtype=td, device=device)
         self.debug = {}
@@ -255,6 +276,8 @@ class RankForward:
         a.T, a.H, a.I, a.k = T, H, I, k
         a.renormalize = int(renormalize)
         a.w_gate, a.w_up, a.w_down = (p.data_ptr() for p in self._ptrs)
+        if self._packed is not None:
+            a.w_gateup_packed, a.w_down_packed = self._packed[1].data_ptr(), self._packed[2].data_ptr()
         a.out = self.out.data_ptr()
         for name, t in self.debug.items():
             setattr(a, name, t.data_ptr())

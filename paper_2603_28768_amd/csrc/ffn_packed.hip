@@ -1,0 +1,246 @@
+// Grouped SwiGLU expert FFN over pre-packed bf16 weights: the weight-streaming kernels.
+//
+// Under skewed routing most of a rank's slots hold few rows, so the two grouped GEMMs of
+// the expert FFN (Sec. 2.1) mostly stream weights: every weight byte of a live slot has to
+// cross HBM once whatever the slot's row count.  These kernels are built around that:
+//
+//   * Expert weights are re-ordered once, outside the forward, into MFMA fragment order
+//     (craft_pack_weights): for each group of output columns and each 16-wide step of the
+//     contraction, the 32 x 16 block that one v_mfma_f32_32x32x16_bf16 consumes as its row
+//     operand is stored as 64 lanes x 16 bytes.  A wave then reads its weights with one
+//     fully coalesced 1 KiB request per MFMA step, straight into registers: no LDS, no
+//     transposition, and each wave of a workgroup streams a different column group, so no
+//     weight byte is requested twice by a workgroup.  For gate/up a group interleaves 16
+//     gate rows with the 16 up rows of the same output columns, which puts gate and up of
+//     one output into the same lane (accumulator elements v and v+8): SwiGLU is applied in
+//     registers.
+//   * The weight stream runs 16 steps (four 64-wide slabs) ahead of the MFMAs in a
+//     statically indexed register ring, which keeps about 16 KiB per wave in flight.
+//   * The activation rows of a tile (up to 128, gathered through the dispatch permutation
+//     for gate/up) are shared by the four waves through LDS, double buffered, staged through
+//     registers two slabs ahead.  Row fragments beyond the tile's valid rows are skipped
+//     (loads, LDS traffic and MFMAs), so a slot with 20 rows costs a quarter of the matrix
+//     work of a full tile while streaming the same weights.
+//
+// The tile list, its XCD-aware walk and the epilogue layout are those of ffn.hip.
+#include "ffn_common.h"
+
+namespace craft {
+namespace {
+
+constexpr int PW = 16;            // weight steps kept in flight per wave
+constexpr int XROWB = 64 * 2 + 16;
+constexpr int XSTAGEB = 128 * XROWB;
+
+typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global address space
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
+typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
+
+// One 64-wide slab U (0..3) of a group of four: prefetch the activation slab two ahead into
+// XL, run the 4 x NXF MFMAs of this slab against LDS stage U&1 while refilling the weight
+// ring four slabs ahead, then put the next slab (already in XS) into the other LDS stage.
+template <int NXF, int U>
+__device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
+                                            int frag_off, unsigned char *smem, wstream_t wp,
+                                            int64_t wstride, const unsigned short *const (&xp)[NXF],
+                                            bf16x8_t (&wq)[PW], u32x4_t (&XL)[NXF], const u32x4_t (&XS)[NXF],
+                                            f32x16_t (&acc)[NXF]) {
+    // contraction offsets past the row are clamped into it: the weights there are zero
+    const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
+#pragma unroll
+    for (int i = 0; i < NXF; ++i) XL[i] = *(xchunk_t)(xp[i] + koff);
+    const unsigned char *xs = smem + (U & 1) * XSTAGEB;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int ko = frag_off + kk * 32;
+        bf16x8_t xf[NXF];
+#pragma unroll
+        for (int g = 0; g < NXF; ++g) xf[g] = *reinterpret_cast<const bf16x8_t *>(xs + g * 32 * XROWB + ko);
+#pragma unroll
+        for (int g = 0; g < NXF; ++g)
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[U * 4 + kk], xf[g], acc[g], 0, 0, 0);
+        const int nxt = min((ks + 4) * 4 + kk, ksteps - 1);
+        wq[U * 4 + kk] = wp[nxt * wstride];
+    }
+    unsigned char *xn = smem + ((U + 1) & 1) * XSTAGEB;
+#pragma unroll
+    for (int i = 0; i < NXF; ++i)
+        *reinterpret_cast<u32x4_t *>(xn + (lr + 32 * i) * XROWB + kc * 16) = XS[i];
+    __syncthreads();
+}
+
+// One tile with NXF live 32-row activation fragments.  The contraction loop is free of
+// branches around memory operations (indices past the end are clamped instead; the packed
+// weights are zero there), so the hardware's in-order load counter lets the weight ring and
+// the activation staging really stay in flight.
+template <bool GATEUP, int NXF>
+__device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, unsigned char *smem,
+                                            int K, int N, int ngroups, int nk4, int32_t lo_pos) {
+    constexpr int GC = GATEUP ? 16 : 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lr = tid >> 3, kc = tid & 7;
+    const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
+    const int ksteps = nk4 * 16;
+    const int group = t.n0 / GC + wave;
+    const bool wlive = group < ngroups;
+    const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
+    // step-major stream: the fragments of all column groups for one step are adjacent
+    wstream_t wp = (wstream_t)wbase + (int64_t)min(group, ngroups - 1) * 64 + lane;
+    const int64_t wstride = (int64_t)ngroups * 64;
+    const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
+
+    const unsigned short *xp[NXF];
+#pragma unroll
+    for (int i = 0; i < NXF; ++i) {
+        const int rr = min(lr + 32 * i, t.rows - 1);
+        const int32_t pos = t.pos0 + t.m0 + rr;
+        if (GATEUP) xp[i] = xin + (int64_t)(a.src[pos] / a.k) * K;
+        else xp[i] = xin + (int64_t)(pos - lo_pos) * K;
+    }
+
+    f32x16_t acc[NXF];
+#pragma unroll
+    for (int g = 0; g < NXF; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+
+    bf16x8_t wq[PW];
+    u32x4_t xa[NXF], xb[NXF];
+#pragma unroll
+    for (int j = 0; j < PW; ++j) wq[j] = wp[j * wstride];
+    {
+        const int k0 = min(kc * 8, K - 8), k1 = min(64 + kc * 8, K - 8);
+#pragma unroll
+        for (int i = 0; i < NXF; ++i) {
+            xa[i] = *(xchunk_t)(xp[i] + k0);
+            xb[i] = *(xchunk_t)(xp[i] + k1);
+        }
+#pragma unroll
+        for (int i = 0; i < NXF; ++i)
+            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xa[i];
+    }
+    __syncthreads();
+
+    const int last_slab = nk4 * 4 - 1;
+    for (int ks = 0; ks <= last_slab; ks += 4) {
+        packed_slab<NXF, 0>(ks + 0, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
+        packed_slab<NXF, 1>(ks + 1, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
+        packed_slab<NXF, 2>(ks + 2, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
+        packed_slab<NXF, 3>(ks + 3, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
+    }
+
+    // epilogue.  Accumulator element v of lane l belongs to weight row
+    // (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of fragment g.
+    if (!wlive) return;
+    unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
+    const int cbase = group * GC;
+#pragma unroll
+    for (int g = 0; g < NXF; ++g) {
+        const int m = g * 32 + (lane & 31);
+        if (m >= t.rows) continue;
+        unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + m - lo_pos) * N;
+        // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
+#pragma unroll
+        for (int vg = 0; vg < (GATEUP ? 2 : 4); ++vg) {
+            const int col = cbase + vg * 8 + (lane >> 5) * 4;
+            if (col >= N) continue;
+            uint32_t h[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                h[c] = GATEUP ? bf16_rne(silu(acc[g][vg * 4 + c]) * acc[g][8 + vg * 4 + c])
+                              : bf16_rne(acc[g][vg * 4 + c]);
+            *reinterpret_cast<uint2 *>(orow + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+        }
+    }
+}
+
+template <bool GATEUP>
+__global__ __launch_bounds__(256, 2) void ffn_packed_kernel(FfnArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XSTAGEB];
+    const int K = GATEUP ? a.H : a.I;
+    const int N = GATEUP ? a.I : a.H;
+    constexpr int GC = GATEUP ? 16 : 32;           // output columns per weight group
+    constexpr int BN = 4 * GC;                     // output columns per tile (one group per wave)
+    const int ngroups = (N + GC - 1) / GC;
+    const int nt = (N + BN - 1) / BN;
+    const int nk4 = (K + 255) / 256;               // groups of four 64-wide slabs
+    const int64_t total = (int64_t)a.mt_start[a.nslots] * nt;
+    const int32_t lo_pos = a.slot_off[a.s_lo];
+
+    for (int64_t w = xcd_major_id(); w < total; w += gridDim.x) {
+        const Tile t = decode_tile(a, w, nt, kBM_bf16, BN);
+        switch ((t.rows + 31) >> 5) {              // live 32-row fragments of this tile
+            case 1: packed_tile<GATEUP, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            case 2: packed_tile<GATEUP, 2>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            case 3: packed_tile<GATEUP, 3>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            default: packed_tile<GATEUP, 4>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+        }
+    }
+}
+
+// One 16-byte chunk of the packed stream per thread.
+//   gate/up : group g = output columns 16g..16g+15; fragment row r < 16 is gate row 16g+r,
+//             r >= 16 is up row 16g+r-16
+//   down    : group g = output columns 32g..32g+31; fragment row r is down row 32g+r
+// Lane l of step s holds fragment row (l & 31), contraction elements 16s + 8(l>>5) .. +7.
+// Rows and contraction elements past the matrix are zero.
+__global__ void pack_kernel(const unsigned short *wa, const unsigned short *wb, int rows, int K,
+                            int gc, int64_t nchunks, int ksteps, uint4 *out) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= nchunks) return;
+    const int l = (int)(c & 63);
+    const int64_t sg = c >> 6;                   // step-major: chunk = (step * ngroups + group) * 64 + lane
+    const int64_t ngroups = nchunks / 64 / ksteps;
+    const int s = (int)(sg / ngroups);
+    const int64_t g = sg % ngroups;
+    const int r = l & 31;
+    const int k0 = 16 * s + 8 * (l >> 5);
+    int64_t row;
+    const unsigned short *src;
+    if (gc == 16) { row = g * 16 + (r & 15); src = r < 16 ? wa : wb; }
+    else { row = g * 32 + r; src = wa; }
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (row < rows && k0 < K) v = *reinterpret_cast<const uint4 *>(src + row * K + k0);
+    out[c] = v;
+}
+
+template <bool GATEUP>
+hipError_t launch_packed(const FfnArgs &a, hipStream_t s) {
+    if (a.nslots <= 0 || a.max_rows <= 0) return hipSuccess;
+    const int N = GATEUP ? a.I : a.H;
+    const int bn = GATEUP ? 64 : 128;
+    const int64_t nt = (N + bn - 1) / bn;
+    const int64_t bound = (a.max_rows / kBM_bf16 + a.nslots) * nt;
+    int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu * 2);
+    grid = std::max<int64_t>(8, (grid + 7) / 8 * 8);
+    hipLaunchKernelGGL(ffn_packed_kernel<GATEUP>, dim3((unsigned)grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gateup_packed(const FfnArgs &a, hipStream_t s) { return launch_packed<true>(a, s); }
+hipError_t launch_down_packed(const FfnArgs &a, hipStream_t s) { return launch_packed<false>(a, s); }
+
+void packed_sizes(int32_t H, int32_t I, size_t *gateup_bytes, size_t *down_bytes) {
+    const size_t gu_groups = (size_t)(I + 15) / 16, gu_steps = (size_t)(H + 255) / 256 * 16;
+    const size_t dn_groups = (size_t)(H + 31) / 32, dn_steps = (size_t)(I + 255) / 256 * 16;
+    *gateup_bytes = gu_groups * gu_steps * 1024;
+    *down_bytes = dn_groups * dn_steps * 1024;
+}
+
+hipError_t launch_pack(int32_t H, int32_t I, const void *wg, const void *wu, const void *wd,
+                       void *pgu, void *pdn, hipStream_t s) {
+    size_t gub, dnb;
+    packed_sizes(H, I, &gub, &dnb);
+    const int64_t c1 = (int64_t)(gub / 16), c2 = (int64_t)(dnb / 16);
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((c1 + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const unsigned short *>(wg), static_cast<const unsigned short *>(wu),
+                       I, H, 16, c1, (H + 255) / 256 * 16, static_cast<uint4 *>(pgu));
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((c2 + 255) / 256)), dim3(256), 0, s,
+                       static_cast<const unsigned short *>(wd), static_cast<const unsigned short *>(wd),
+                       H, I, 32, c2, (I + 255) / 256 * 16, static_cast<uint4 *>(pdn));
+    return hipGetLastError();
+}
+
+}  // namespace craft

@@ -146,6 +146,26 @@ craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t
     return CRAFT_OK;
 }
 
+craft_status craft_pack_weights_bytes(int32_t dtype, int32_t H, int32_t I, size_t *gateup_bytes,
+                                      size_t *down_bytes) {
+    if (dtype != CRAFT_BF16 || H <= 0 || I <= 0 || H % 8 || I % 8 || !gateup_bytes || !down_bytes)
+        return CRAFT_EINVAL;
+    packed_sizes(H, I, gateup_bytes, down_bytes);
+    return CRAFT_OK;
+}
+
+craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void *w_gate,
+                                const void *w_up, const void *w_down, void *packed_gateup,
+                                void *packed_down, void *stream) {
+    if (dtype != CRAFT_BF16 || H <= 0 || I <= 0 || H % 8 || I % 8) return CRAFT_EINVAL;
+    if (!w_gate || !w_up || !w_down || !packed_gateup || !packed_down) return CRAFT_EINVAL;
+    if (!aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(w_down, 16) ||
+        !aligned(packed_gateup, 16) || !aligned(packed_down, 16))
+        return CRAFT_EINVAL;
+    return launch_pack(H, I, w_gate, w_up, w_down, packed_gateup, packed_down, as_stream(stream)) ==
+                   hipSuccess ? CRAFT_OK : CRAFT_EHIP;
+}
+
 craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                               const craft_fwd_args *a, size_t *bytes) {
     if (!bytes) return CRAFT_EINVAL;
@@ -181,7 +201,10 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     if (a->T > 0) {
         if (!a->x || !a->logits || !a->out) return CRAFT_EINVAL;
         if (!aligned(a->x, 16) || !aligned(a->out, 16) || !aligned(a->logits, 4)) return CRAFT_EINVAL;
-        if (nslots > 0 && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
+        const bool packed = a->w_gateup_packed && a->w_down_packed;
+        if ((a->w_gateup_packed != nullptr) != (a->w_down_packed != nullptr)) return CRAFT_EINVAL;
+        if (packed && a->dtype != CRAFT_BF16) return CRAFT_EINVAL;
+        if (nslots > 0 && !packed && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
     }
     hipStream_t s = as_stream(stream);
     unsigned char *ws = static_cast<unsigned char *>(a->workspace);
@@ -224,15 +247,19 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     }
     // 4 grouped FFN
     FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, ctrl,
-               a->w_gate, a->w_up, a->w_down, ws + L.act, ws + L.y, L.max_rows, cached_num_cu()};
+               a->w_gate, a->w_up, a->w_down, a->w_gateup_packed, a->w_down_packed,
+               ws + L.act, ws + L.y, L.max_rows, cached_num_cu()};
     if (a->T > 0) {
+        const bool packed = a->w_gateup_packed && a->w_down_packed;
         {
             ScopedEvent ev(CRAFT_K_GATEUP, s);
-            if (launch_gateup(fa, s) != hipSuccess) return CRAFT_EHIP;
+            if ((packed ? launch_gateup_packed(fa, s) : launch_gateup(fa, s)) != hipSuccess)
+                return CRAFT_EHIP;
         }
         {
             ScopedEvent ev(CRAFT_K_DOWN, s);
-            if (launch_down(fa, s) != hipSuccess) return CRAFT_EHIP;
+            if ((packed ? launch_down_packed(fa, s) : launch_down(fa, s)) != hipSuccess)
+                return CRAFT_EHIP;
         }
     }
     // 5 combine

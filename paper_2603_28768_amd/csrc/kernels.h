@@ -71,7 +71,8 @@ struct FfnArgs {
     const int32_t *slot_off;       // [S+1]
     const int32_t *mt_start;       // [nslots+1]
     const int32_t *ctrl;
-    const void *const *w_gate, *const *w_up, *const *w_down;
+    const void *const *w_gate, *const *w_up, *const *w_down;   // row-major weights per slot
+    const void *const *wp_gateup, *const *wp_down;             // fragment-packed weights per slot
     void *act;                     // [max_rows][I] SwiGLU activations
     void *y;                       // [max_rows][H]
     int64_t max_rows;
@@ -79,6 +80,11 @@ struct FfnArgs {
 };
 hipError_t launch_gateup(const FfnArgs &a, hipStream_t s);
 hipError_t launch_down(const FfnArgs &a, hipStream_t s);
+hipError_t launch_gateup_packed(const FfnArgs &a, hipStream_t s);
+hipError_t launch_down_packed(const FfnArgs &a, hipStream_t s);
+void packed_sizes(int32_t H, int32_t I, size_t *gateup_bytes, size_t *down_bytes);
+hipError_t launch_pack(int32_t H, int32_t I, const void *wg, const void *wu, const void *wd,
+                       void *pgu, void *pdn, hipStream_t s);
 
 struct CombineArgs {
     int32_t dtype;

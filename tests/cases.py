@@ -47,19 +47,26 @@ class Case:
         return oracle.rank_forward(self.x, self.logits, self.cfg.k, self.slot_expert,
                                    self.rank_slot_off, rank, self.weights_of, True, tokens)
 
-    def gpu_rank(self, rank: int, max_rows: int = 0, debug: bool = True, device="cuda:0"):
-        """(RankForward, x_dev, logits_dev) with this rank's weights resident."""
+    def gpu_rank(self, rank: int, max_rows: int = 0, debug: bool = True, device="cuda:0",
+                 packed: bool = False):
+        """(RankForward, x_dev, logits_dev) with this rank's weights resident; packed=True
+        re-orders the weights with craft_pack_weights and runs the weight-streaming kernels."""
         import torch
         cfg = self.cfg
-        wg, wu, wd = [], [], []
-        dev_cache = {}
+        wg, wu, wd, pk = [], [], [], []
+        dev_cache, pack_cache = {}, {}
         for e in self.rank_slots(rank):
             if e not in dev_cache:
                 dev_cache[e] = tuple(binding.to_device(m, cfg.dtype, device) for m in self.weights_of(e))
+                if packed:
+                    pack_cache[e] = binding.pack_weights(*dev_cache[e])
             g, u, d = dev_cache[e]
             wg.append(g); wu.append(u); wd.append(d)
+            if packed:
+                pk.append(pack_cache[e])
         fwd = binding.RankForward(self.plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
-                                  wg, wu, wd, True, max_rows, device, want_debug_outputs=debug)
+                                  wg, wu, wd, True, max_rows, device, want_debug_outputs=debug,
+                                  packed=pk if packed else None)
         x = binding.to_device(self.x, cfg.dtype, device)
         logits = torch.from_numpy(self.logits).to(device)
         return fwd, x, logits

@@ -85,9 +85,9 @@ def test_expert_load_on_a_zipf_trace(torch_cuda):
 
 # --------------------------------------------------------------------- forward
 
-def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0):
+def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False):
     cfg = case.cfg
-    fwd, x, logits = case.gpu_rank(rank, max_rows)
+    fwd, x, logits = case.gpu_rank(rank, max_rows, packed=packed)
     out = fwd(x, logits)
     rows, ovf = fwd.result()
     ref = case.oracle_rank(rank, tokens)
@@ -105,7 +105,7 @@ def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0):
         got = got[np.asarray(tokens)]
     scale = np.abs(ref["out"]).max()
     err = np.abs(got - ref["out"]).max()
-    print(f"  rank {rank}: rows={rows} max|ref|={scale:.4g} max|err|={err:.3g} "
+    print(f"  rank {rank} packed={packed}: rows={rows} max|ref|={scale:.4g} max|err|={err:.3g} "
           f"rel={err / max(scale, 1e-30):.3g}", flush=True)
     assert err <= TOL[cfg.dtype] * scale + 1e-30
     return _np(out).astype(np.float64), ref
@@ -139,6 +139,8 @@ def test_reduced_layers_every_rank(torch_cuda, dtype, T, H, I, E, k, D, slots):
     case = Case(cfg)
     for g in range(D):
         _check_rank(torch_cuda, case, g)
+        if dtype == "bf16":
+            _check_rank(torch_cuda, case, g, packed=True)
 
 
 def test_forward_is_reproducible_bit_for_bit(torch_cuda):
@@ -146,7 +148,7 @@ def test_forward_is_reproducible_bit_for_bit(torch_cuda):
     cfg = synth.scaled(synth.CONFIGS["qwen3"], T=700, H=256, I=256, E=32, D=4, replica_slots=4,
                        profile_batches=2)
     case = Case(cfg)
-    fwd, x, logits = case.gpu_rank(case.heaviest)
+    fwd, x, logits = case.gpu_rank(case.heaviest, packed=True)
     a = fwd(x, logits).clone()
     da = {k: v.clone() for k, v in fwd.debug.items()}
     for _ in range(3):
@@ -164,9 +166,41 @@ def test_rank_without_rows_and_unused_experts(torch_cuda):
     case = Case(cfg)
     assert min(case.rows) == 0
     for g in (int(np.argmin(case.rows)), case.heaviest):
-        out, _ = _check_rank(torch_cuda, case, g)
+        out, _ = _check_rank(torch_cuda, case, g, packed=True)
         if case.rows[g] == 0:
             assert np.all(out == 0)
+
+
+def test_packed_weights_layout(torch_cuda):
+    # the packed stream against its stated layout, element by element
+    torch = torch_cuda
+    H, I = 72, 40                                   # ragged in every direction
+    g = np.random.default_rng(5)
+    mats = [synth.round_to_storage(g.standard_normal(s).astype(np.float32), "bf16")
+            for s in ((I, H), (I, H), (H, I))]
+    dev = [binding.to_device(m, "bf16") for m in mats]
+    pgu, pdn = binding.pack_weights(*dev)
+    torch.cuda.synchronize()
+    pgu = synth.bf16_bits_to_f32(pgu.cpu().numpy().view(np.uint16))
+    pdn = synth.bf16_bits_to_f32(pdn.cpu().numpy().view(np.uint16))
+    Wg, Wu, Wd = mats
+
+    def expect(groups, ksteps, row_of, K):
+        out = np.zeros((ksteps, groups, 64, 8), np.float32)
+        for gi in range(groups):
+            for s in range(ksteps):
+                for l in range(64):
+                    src = row_of(gi, l & 31)
+                    k0 = 16 * s + 8 * (l >> 5)
+                    if src is not None and k0 < K:
+                        out[s, gi, l] = src[k0:k0 + 8]
+        return out.reshape(-1)
+
+    gu = expect((I + 15) // 16, (H + 255) // 256 * 16,
+                lambda gi, r: (Wg if r < 16 else Wu)[16 * gi + (r & 15)] if 16 * gi + (r & 15) < I else None, H)
+    dn = expect((H + 31) // 32, (I + 255) // 256 * 16,
+                lambda gi, r: Wd[32 * gi + r] if 32 * gi + r < H else None, I)
+    assert np.array_equal(pgu, gu) and np.array_equal(pdn, dn)
 
 
 def test_empty_batch(torch_cuda):
@@ -240,4 +274,5 @@ def test_full_size_heaviest_rank_sampled(torch_cuda, name):
     print(f"  rows per rank: max={max(case.rows)} mean={np.mean(case.rows):.0f} heaviest={g} "
           f"slots={case.rank_slots(g)}", flush=True)
     toks = _sampled_tokens(case, g, 12)
-    _check_rank(torch_cuda, case, g, tokens=toks)
+    _check_rank(torch_cuda, case, g, tokens=toks, packed=True)
+    _check_rank(torch_cuda, case, g, tokens=toks, packed=False)
