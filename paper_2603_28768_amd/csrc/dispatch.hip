@@ -15,54 +15,65 @@ namespace {
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
 
-// Exclusive scan of n values produced by `get(i)`, written through `put(i, prefix)`;
-// returns the total to every thread.  Each thread owns a contiguous run of items.
-template <typename Get, typename Put>
-__device__ int32_t block_exclusive_scan(int32_t n, int32_t *sh /*[kScanThreads]*/, Get get, Put put) {
-    const int tid = threadIdx.x;
-    const int32_t per = (n + kScanThreads - 1) / kScanThreads;
-    const int32_t lo = min(n, tid * per), hi = min(n, lo + per);
-    int32_t sum = 0;
-    for (int32_t i = lo; i < hi; ++i) sum += get(i);
-    sh[tid] = sum;
-    __syncthreads();
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        int32_t v = tid >= off ? sh[tid - off] : 0;
-        __syncthreads();
-        sh[tid] += v;
-        __syncthreads();
+// Exclusive scan over the workgroup of one value per thread (wave shuffles, then one LDS
+// exchange between the 16 waves).  Returns the exclusive prefix; *total gets the sum.
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum /*[kScanWaves]*/,
+                                                        int32_t *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int32_t o = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += o;
     }
-    const int32_t total = sh[kScanThreads - 1];
-    int32_t run = sh[tid] - sum;
-    for (int32_t i = lo; i < hi; ++i) {
-        const int32_t v = get(i);
-        put(i, run);
-        run += v;
-    }
+    __syncthreads();                       // wsum may still be read from an earlier scan
+    if (lane == 63) wsum[wave] = inc;
     __syncthreads();
-    return total;
+    int32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) {
+        const int32_t s = wsum[w];
+        if (w < wave) before += s;
+        all += s;
+    }
+    *total = all;
+    return before + inc - v;
 }
 
 // One workgroup per 64 experts.  Wave w owns a contiguous range of blocks; a lane owns one
-// expert.  Pass 1 sums the range, the waves' sums are prefix-combined through LDS, pass 2
-// rewrites the per-block counts as exclusive prefixes.  The workgroup that finishes last
-// (ticket counter) derives everything that needs all counts: rows per slot, slot offsets,
-// the rank's row count and the row-tile table of the grouped GEMMs.
+// expert.  Each wave sums its range, the waves' sums are prefix-combined through LDS, and
+// the per-block counts are rewritten as exclusive prefixes.  The workgroup that finishes
+// last (ticket counter) derives everything that needs all counts: rows per slot, slot
+// offsets, the rank's row count and the row-tile table of the grouped GEMMs.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
-    __shared__ int32_t sh[kScanThreads];
     __shared__ int32_t part[kScanWaves][64];
+    __shared__ int32_t wsum[kScanWaves];
+    __shared__ int32_t cnt_lds[1024];
     __shared__ int32_t last_flag;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int e = blockIdx.x * 64 + lane;
     const int rows_per_wave = (a.NB + kScanWaves - 1) / kScanWaves;
     const int b0 = min(a.NB, wave * rows_per_wave), b1 = min(a.NB, b0 + rows_per_wave);
 
+    // the common case keeps a wave's block counts in registers between the two passes
+    constexpr int kKeep = 16;
+    int32_t keep[kKeep];
     int32_t sum = 0;
-    if (e < a.E)
-        for (int b = b0; b < b1; ++b) sum += a.hist[(int64_t)b * a.E + e];
+    if (e < a.E) {
+        if (rows_per_wave <= kKeep) {
+#pragma unroll
+            for (int i = 0; i < kKeep; ++i) {
+                keep[i] = b0 + i < b1 ? a.hist[(int64_t)(b0 + i) * a.E + e] : 0;
+                sum += keep[i];
+            }
+        } else {
+            for (int b = b0; b < b1; ++b) sum += a.hist[(int64_t)b * a.E + e];
+        }
+    }
     part[wave][lane] = sum;
     __syncthreads();
     int32_t before = 0, total = 0;
+#pragma unroll
     for (int w = 0; w < kScanWaves; ++w) {
         const int32_t v = part[w][lane];
         if (w < wave) before += v;
@@ -70,11 +81,17 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     }
     if (e < a.E) {
         int32_t run = before;
-        for (int b = b0; b < b1; ++b) {
-            int32_t *p = a.hist + (int64_t)b * a.E + e;
-            const int32_t v = *p;
-            *p = run;
-            run += v;
+        if (rows_per_wave <= kKeep) {
+#pragma unroll
+            for (int i = 0; i < kKeep; ++i)
+                if (b0 + i < b1) { a.hist[(int64_t)(b0 + i) * a.E + e] = run; run += keep[i]; }
+        } else {
+            for (int b = b0; b < b1; ++b) {
+                int32_t *p = a.hist + (int64_t)b * a.E + e;
+                const int32_t v = *p;
+                *p = run;
+                run += v;
+            }
         }
         if (wave == 0) {
             a.counts[e] = total;
@@ -97,49 +114,57 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     const int32_t *copies = a.tables + hdr->off_copies;
     const int32_t *slot_expert = a.tables + hdr->off_slot_expert;
     const int32_t *slot_copy = a.tables + hdr->off_slot_copy;
-    const int32_t *counts = a.counts;
-
-    // rows of slot p: tokens i < n of its expert with i mod c == q
-    auto slot_rows = [&](int32_t p) -> int32_t {
-        const int32_t ex = slot_expert[p];
-        const int32_t n = __hip_atomic_load(counts + ex, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int32_t c = copies[ex], q = slot_copy[p];
-        return n > q ? (n - q + c - 1) / c : 0;
-    };
-    const int32_t all = block_exclusive_scan(
-        a.S, sh, slot_rows, [&](int32_t p, int32_t pre) {
-            a.slot_off[p] = pre;
-            if (a.user_slot_off) a.user_slot_off[p] = pre;
-        });
-    for (int32_t p = threadIdx.x; p < a.S; p += kScanThreads) {
-        const int32_t r = slot_rows(p);
-        a.slot_cnt[p] = r;
-        if (a.user_slot_cnt) a.user_slot_cnt[p] = r;
-    }
-    if (threadIdx.x == 0) {
-        a.slot_off[a.S] = all;
-        if (a.user_slot_off) a.user_slot_off[a.S] = all;
-    }
-    // this rank's rows; refuse the batch when they exceed the staging buffers
-    __shared__ int32_t rank_rows, overflow;
-    if (threadIdx.x == 0) {
-        int32_t r = 0;
-        for (int32_t p = a.s_lo; p < a.s_hi; ++p) r += slot_rows(p);
-        rank_rows = r;
-        overflow = (int64_t)r > a.max_rows;
-    }
+    for (int32_t i = threadIdx.x; i < a.E; i += kScanThreads)
+        cnt_lds[i] = __hip_atomic_load(a.counts + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    const bool ovf = overflow != 0;
-    const int32_t nslots = a.s_hi - a.s_lo;
-    const int32_t mtiles = block_exclusive_scan(
-        nslots, sh,
-        [&](int32_t s) -> int32_t { return ovf ? 0 : (slot_rows(a.s_lo + s) + a.bm - 1) / a.bm; },
-        [&](int32_t s, int32_t pre) { a.mt_start[s] = pre; });
+
+    // rows of slot p: tokens i < n of its expert with i mod c == q.  Slots are taken in
+    // chunks of one per thread; `carry` is the running offset across chunks.
+    int32_t carry = 0, lo_pos = 0, hi_pos = 0;
+    for (int32_t base = 0; base < a.S; base += kScanThreads) {
+        const int32_t p = base + threadIdx.x;
+        int32_t r = 0;
+        if (p < a.S) {
+            const int32_t ex = slot_expert[p];
+            const int32_t n = cnt_lds[ex], c = copies[ex], q = slot_copy[p];
+            r = n > q ? (n - q + c - 1) / c : 0;
+        }
+        int32_t chunk_total;
+        const int32_t off = carry + block_exclusive_scan(r, wsum, &chunk_total);
+        if (p < a.S) {
+            a.slot_cnt[p] = r;
+            a.slot_off[p] = off;
+            if (a.user_slot_cnt) a.user_slot_cnt[p] = r;
+            if (a.user_slot_off) a.user_slot_off[p] = off;
+        }
+        carry += chunk_total;
+    }
     if (threadIdx.x == 0) {
-        a.mt_start[nslots] = mtiles;
+        a.slot_off[a.S] = carry;
+        if (a.user_slot_off) a.user_slot_off[a.S] = carry;
+    }
+    __syncthreads();                       // this workgroup's slot_off stores, visible to itself
+    lo_pos = a.s_lo < a.S ? a.slot_off[a.s_lo] : carry;
+    hi_pos = a.s_hi < a.S ? a.slot_off[a.s_hi] : carry;
+    // this rank's rows; refuse the batch when they exceed the staging buffers
+    const int32_t rank_rows = hi_pos - lo_pos;
+    const bool ovf = (int64_t)rank_rows > a.max_rows;
+    const int32_t nslots = a.s_hi - a.s_lo;
+    int32_t mcarry = 0;
+    for (int32_t base = 0; base < nslots; base += kScanThreads) {
+        const int32_t sl = base + threadIdx.x;
+        int32_t mt = 0;
+        if (sl < nslots && !ovf) mt = (a.slot_cnt[a.s_lo + sl] + a.bm - 1) / a.bm;
+        int32_t chunk_total;
+        const int32_t off = mcarry + block_exclusive_scan(mt, wsum, &chunk_total);
+        if (sl < nslots) a.mt_start[sl] = off;
+        mcarry += chunk_total;
+    }
+    if (threadIdx.x == 0) {
+        a.mt_start[nslots] = mcarry;
         a.ctrl[CTRL_ROWS] = rank_rows;
-        a.ctrl[CTRL_OVERFLOW] = overflow;
-        a.ctrl[CTRL_MTILES] = mtiles;
+        a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
+        a.ctrl[CTRL_MTILES] = mcarry;
         a.ctrl[CTRL_TICKET] = 0;
     }
 }

@@ -58,9 +58,9 @@ __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, i
         for (int g = 0; g < NXF; ++g) xf[g] = *reinterpret_cast<const bf16x8_t *>(xs + g * 32 * XROWB + ko);
 #pragma unroll
         for (int g = 0; g < NXF; ++g)
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[U * 4 + kk], xf[g], acc[g], 0, 0, 0);
-        const int nxt = min((ks + 4) * 4 + kk, ksteps - 1);
-        wq[U * 4 + kk] = wp[nxt * wstride];
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[(U * 4 + kk) % PW], xf[g], acc[g], 0, 0, 0);
+        const int nxt = min(ks * 4 + kk + PW, ksteps - 1);
+        wq[(U * 4 + kk) % PW] = wp[nxt * wstride];
     }
     unsigned char *xn = smem + ((U + 1) & 1) * XSTAGEB;
 #pragma unroll

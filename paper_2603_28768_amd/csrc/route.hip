@@ -1,116 +1,179 @@
 // Router softmax / top-k (Sec. 2.1: the gating network scores every expert and the
-// top-K scores are activated), one 64-lane wavefront per token.
+// top-K scores are activated).
 //
-// A lane holds the scores of experts lane, lane+64, ... so a row is read with fully
-// coalesced 256-byte requests.  The k picks are k wave-wide arg-max reductions over
-// (score, expert id) with butterfly shuffles; scores are compared raw (never their
-// exponentials) and equal scores resolve to the lower expert id.
+// A token is handled by one 16-lane DPP row of a 64-lane wavefront, so a wave routes four
+// tokens at once and every cross-lane step is a row-local DPP move (quad permutes and
+// row mirrors), not an LDS permute.  A lane holds the scores of experts 4*lane..4*lane+3,
+// +64, +128, ... (16-byte loads; a token's row is read as contiguous 256-byte pieces).
+// Each of the k picks is an arg-max over (score, expert id): first inside the lane in
+// ascending expert order, then a four-step butterfly over the row.  Scores are compared
+// raw, never their exponentials, and equal scores resolve to the lower expert id.
 //
-// A workgroup covers 32 consecutive tokens.  While the picks are still in registers it
-// also records, per expert, a 32-bit mask of the block's tokens that chose it: the number
-// of set bits below a token's own bit is that assignment's rank among the block's
-// assignments to the expert (experts of one token are distinct), and the population count
-// is the block's contribution to the expert's load.
+// A workgroup covers 32 consecutive tokens (two passes of 16).  While the picks are still in
+// registers it also records, per expert, a 32-bit mask of the block's tokens that chose it:
+// the number of set bits below a token's own bit is that assignment's rank among the
+// block's assignments to the expert (experts of one token are distinct), and the
+// population count is the block's contribution to the expert's load.
 #include "kernels.h"
 
 namespace craft {
 namespace {
 
-constexpr int kWave = 64;
-constexpr int kWavesPerBlock = 4;
-constexpr int kTokPerWave = kTokPerBlock / kWavesPerBlock;
+constexpr int kThreads = 256;
 constexpr int kMaxE = 1024;
+constexpr int kMaxPickSlots = 4;     // k <= 64 picks, 16 lanes per token
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+// lane exchange patterns that together reach every lane of a 16-lane row
+constexpr int kXor1 = 0xB1, kXor2 = 0x4E, kHalfMirror = 0x141, kMirror = 0x140;
 
 __device__ __forceinline__ bool beats(float va, int ia, float vb, int ib) {
-    if (ia < 0) return false;
-    if (ib < 0) return true;
     return va > vb || (va == vb && ia < ib);
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, kWave);
+template <int CTRL>
+__device__ __forceinline__ void argmax_step(float &v, int &i) {
+    const float ov = dpp_f<CTRL>(v);
+    const int oi = dpp_i<CTRL>(i);
+    if (beats(ov, oi, v, i)) { v = ov; i = oi; }
+}
+
+__device__ __forceinline__ float row_sum(float v) {
+    v += dpp_f<kXor1>(v);
+    v += dpp_f<kXor2>(v);
+    v += dpp_f<kHalfMirror>(v);
+    v += dpp_f<kMirror>(v);
     return v;
 }
 
-template <int VPT>
-__global__ __launch_bounds__(kWave * kWavesPerBlock) void route_kernel(RouteArgs a) {
+// NQ = 16-byte score chunks per lane (each chunk = 4 experts; a row covers 64 experts per chunk)
+template <int NQ>
+__global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
     __shared__ uint32_t mask[kMaxE];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x;
+    const int sub = tid & 15;                      // lane inside the token's row
     const bool ranks = a.hist != nullptr;
+    const bool vec_ok = (a.E & 3) == 0;            // rows 16-byte aligned
 
     if (ranks) {
-        for (int e = threadIdx.x; e < a.E; e += blockDim.x) mask[e] = 0u;
-        if (a.ctrl && blockIdx.x == 0 && threadIdx.x < CTRL_WORDS) a.ctrl[threadIdx.x] = 0;
+        for (int e = tid; e < a.E; e += kThreads) mask[e] = 0u;
+        if (a.ctrl && blockIdx.x == 0 && tid < CTRL_WORDS) a.ctrl[tid] = 0;
         __syncthreads();
     }
 
-    int my_id[kTokPerWave];
+    int my_id[2][kMaxPickSlots];
 #pragma unroll
-    for (int it = 0; it < kTokPerWave; ++it) {
-        my_id[it] = -1;
-        const int tl = wave * kTokPerWave + it;
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int s = 0; s < kMaxPickSlots; ++s) my_id[pass][s] = -1;
+        const int tl = pass * 16 + (tid >> 4);     // token inside the block
         const int64_t t = (int64_t)blockIdx.x * kTokPerBlock + tl;
-        if (t >= a.T) continue;                       // uniform over the wave
-        const float *row = a.logits + t * a.E;
-        float v[VPT];
+        const bool live = t < a.T;                 // uniform over the row
+        const float *row = a.logits + (live ? t : 0) * a.E;
+
+        float v[NQ][4];
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            const int e = lane + kWave * i;
-            v[i] = e < a.E ? row[e] : 0.0f;
-        }
-        uint32_t taken = 0u;
-        float pick_v = 0.0f;
-        int pick_i = -1;
-        for (int j = 0; j < a.k; ++j) {
-            float bv = 0.0f;
-            int bi = -1;
+        for (int q = 0; q < NQ; ++q) {
+            const int e0 = q * 64 + sub * 4;
+            if (vec_ok && e0 + 3 < a.E) {
+                const float4 f = *reinterpret_cast<const float4 *>(row + e0);
+                v[q][0] = f.x; v[q][1] = f.y; v[q][2] = f.z; v[q][3] = f.w;
+            } else {
 #pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                const int e = lane + kWave * i;
-                if (e < a.E && !((taken >> i) & 1u) && (bi < 0 || v[i] > bv)) { bv = v[i]; bi = e; }
+                for (int c = 0; c < 4; ++c) v[q][c] = e0 + c < a.E ? row[e0 + c] : 0.0f;
             }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bv, off, kWave);
-                const int oi = __shfl_xor(bi, off, kWave);
-                if (beats(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-            }
-            if ((bi & (kWave - 1)) == lane) taken |= 1u << (bi >> 6);
-            if (lane == j) { pick_v = bv; pick_i = bi; }
         }
-        // softmax weight of the picks; the first pick carries the row maximum
-        const float mx = __shfl(pick_v, 0, kWave);
-        const float ex = lane < a.k ? expf(pick_v - mx) : 0.0f;
-        float den;
-        if (a.renorm) {
-            den = wave_sum(ex);
+        // bit (q*4+c) set = that expert is still available to this lane
+        uint64_t avail = 0;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (q * 64 + sub * 4 + c < a.E) avail |= 1ull << (q * 4 + c);
+
+        float pick_v[kMaxPickSlots];
+        float first_v = 0.0f;
+#pragma unroll
+        for (int s = 0; s < kMaxPickSlots; ++s) {
+            pick_v[s] = 0.0f;
+            const int jn = min(16, a.k - s * 16);  // picks that land in slot s
+            for (int j = 0; j < jn; ++j) {
+                float bv = 0.0f;
+                int bi = 0x7fffffff;               // no candidate: loses every comparison
+                bool have = false;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (((avail >> (q * 4 + c)) & 1ull) && (!have || v[q][c] > bv)) {
+                            bv = v[q][c];
+                            bi = q * 64 + sub * 4 + c;
+                            have = true;
+                        }
+                if (!have) bv = -__builtin_huge_valf();
+                argmax_step<kXor1>(bv, bi);
+                argmax_step<kXor2>(bv, bi);
+                argmax_step<kHalfMirror>(bv, bi);
+                argmax_step<kMirror>(bv, bi);
+                // the owner retires the pick; lane j of the row keeps it for the output
+                if (((bi >> 2) & 15) == sub) avail &= ~(1ull << ((bi >> 6) * 4 + (bi & 3)));
+                if (j == sub) { pick_v[s] = bv; my_id[pass][s] = bi; }
+                if (s == 0 && j == 0) first_v = bv;       // the row maximum
+            }
+        }
+        // softmax weight of the picks
+        float ex[kMaxPickSlots], part = 0.0f;
+#pragma unroll
+        for (int s = 0; s < kMaxPickSlots; ++s) {
+            ex[s] = s * 16 + sub < a.k ? expf(pick_v[s] - first_v) : 0.0f;
+            part += ex[s];
+        }
+        if (!a.renorm) {
+            part = 0.0f;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (q * 64 + sub * 4 + c < a.E) part += expf(v[q][c] - first_v);
+        }
+        const float den = row_sum(part);
+        if (live) {
+#pragma unroll
+            for (int s = 0; s < kMaxPickSlots; ++s) {
+                const int j = s * 16 + sub;
+                if (j < a.k) {
+                    a.ids[t * a.k + j] = my_id[pass][s];
+                    a.w[t * a.k + j] = ex[s] / den;
+                    if (ranks) atomicOr(&mask[my_id[pass][s]], 1u << tl);
+                }
+            }
         } else {
-            float s = 0.0f;
 #pragma unroll
-            for (int i = 0; i < VPT; ++i)
-                if (lane + kWave * i < a.E) s += expf(v[i] - mx);
-            den = wave_sum(s);
-        }
-        if (lane < a.k) {
-            a.ids[t * a.k + lane] = pick_i;
-            a.w[t * a.k + lane] = ex / den;
-            my_id[it] = pick_i;
-            if (ranks) atomicOr(&mask[pick_i], 1u << tl);
+            for (int s = 0; s < kMaxPickSlots; ++s) my_id[pass][s] = -1;
         }
     }
     if (!ranks) return;
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kTokPerWave; ++it) {
-        const int tl = wave * kTokPerWave + it;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = pass * 16 + (tid >> 4);
         const int64_t t = (int64_t)blockIdx.x * kTokPerBlock + tl;
-        if (t < a.T && lane < a.k)
-            a.lrank[t * a.k + lane] = (uint8_t)__popc(mask[my_id[it]] & ((1u << tl) - 1u));
+#pragma unroll
+        for (int s = 0; s < kMaxPickSlots; ++s) {
+            const int j = s * 16 + sub;
+            if (t < a.T && j < a.k)
+                a.lrank[t * a.k + j] = (uint8_t)__popc(mask[my_id[pass][s]] & ((1u << tl) - 1u));
+        }
     }
     int32_t *hrow = a.hist + (int64_t)blockIdx.x * a.E;
-    for (int e = threadIdx.x; e < a.E; e += blockDim.x) hrow[e] = __popc(mask[e]);
+    for (int e = tid; e < a.E; e += kThreads) hrow[e] = __popc(mask[e]);
 }
 
 __global__ void clear_ctrl_kernel(int32_t *ctrl) {
@@ -127,13 +190,13 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t s) {
         return hipGetLastError();
     }
     const int64_t nb = (a.T + kTokPerBlock - 1) / kTokPerBlock;
-    dim3 grid((unsigned)nb), block(kWave * kWavesPerBlock);
-    const int vpt = (a.E + kWave - 1) / kWave;
-    if (vpt <= 1) hipLaunchKernelGGL(route_kernel<1>, grid, block, 0, s, a);
-    else if (vpt <= 2) hipLaunchKernelGGL(route_kernel<2>, grid, block, 0, s, a);
-    else if (vpt <= 4) hipLaunchKernelGGL(route_kernel<4>, grid, block, 0, s, a);
-    else if (vpt <= 6) hipLaunchKernelGGL(route_kernel<6>, grid, block, 0, s, a);
-    else if (vpt <= 8) hipLaunchKernelGGL(route_kernel<8>, grid, block, 0, s, a);
+    dim3 grid((unsigned)nb), block(kThreads);
+    const int nq = (a.E + 63) / 64;
+    if (nq <= 1) hipLaunchKernelGGL(route_kernel<1>, grid, block, 0, s, a);
+    else if (nq <= 2) hipLaunchKernelGGL(route_kernel<2>, grid, block, 0, s, a);
+    else if (nq <= 4) hipLaunchKernelGGL(route_kernel<4>, grid, block, 0, s, a);
+    else if (nq <= 6) hipLaunchKernelGGL(route_kernel<6>, grid, block, 0, s, a);
+    else if (nq <= 8) hipLaunchKernelGGL(route_kernel<8>, grid, block, 0, s, a);
     else hipLaunchKernelGGL(route_kernel<16>, grid, block, 0, s, a);
     return hipGetLastError();
 }
