@@ -150,14 +150,31 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     const int32_t rank_rows = hi_pos - lo_pos;
     const bool ovf = (int64_t)rank_rows > a.max_rows;
     const int32_t nslots = a.s_hi - a.s_lo;
+    // Order the rank's slots by rows, busiest first (ties: lower slot), so the tile list
+    // starts with the matrix-bound tiles and ends with the cheap weight-streaming ones.
+    __shared__ int32_t sorted_rows[1024];
+    __syncthreads();
+    for (int32_t sl = threadIdx.x; sl < nslots; sl += kScanThreads) cnt_lds[sl] = a.slot_cnt[a.s_lo + sl];
+    __syncthreads();
+    for (int32_t sl = threadIdx.x; sl < nslots; sl += kScanThreads) {
+        const int32_t mine = cnt_lds[sl];
+        int32_t pos = 0;
+        for (int32_t j = 0; j < nslots; ++j) {
+            const int32_t other = cnt_lds[j];
+            pos += (other > mine || (other == mine && j < sl)) ? 1 : 0;
+        }
+        a.order[pos] = sl;
+        sorted_rows[pos] = mine;
+    }
+    __syncthreads();
     int32_t mcarry = 0;
     for (int32_t base = 0; base < nslots; base += kScanThreads) {
-        const int32_t sl = base + threadIdx.x;
+        const int32_t pos = base + threadIdx.x;
         int32_t mt = 0;
-        if (sl < nslots && !ovf) mt = (a.slot_cnt[a.s_lo + sl] + a.bm - 1) / a.bm;
+        if (pos < nslots && !ovf) mt = (sorted_rows[pos] + a.bm - 1) / a.bm;
         int32_t chunk_total;
         const int32_t off = mcarry + block_exclusive_scan(mt, wsum, &chunk_total);
-        if (sl < nslots) a.mt_start[sl] = off;
+        if (pos < nslots) a.mt_start[pos] = off;
         mcarry += chunk_total;
     }
     if (threadIdx.x == 0) {

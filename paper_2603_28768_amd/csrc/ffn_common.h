@@ -27,9 +27,9 @@ static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, int64_t w, 
         const int32_t mid = (lo + hi) >> 1;
         if (a.mt_start[mid] <= qn) lo = mid; else hi = mid;
     }
-    const int32_t s = lo;
-    const int32_t mt_first = a.mt_start[s];
-    const int32_t mts = a.mt_start[s + 1] - mt_first;
+    const int32_t mt_first = a.mt_start[lo];
+    const int32_t mts = a.mt_start[lo + 1] - mt_first;
+    const int32_t s = a.order[lo];             // the list is ordered busiest slot first
     const int32_t rem = (int32_t)(w - (int64_t)mt_first * nt);
     Tile t;
     t.slot = s;

@@ -1,50 +1,63 @@
 // Grouped SwiGLU expert FFN over pre-packed bf16 weights: the weight-streaming kernels.
 //
-// Under skewed routing most of a rank's slots hold few rows, so the two grouped GEMMs of
-// the expert FFN (Sec. 2.1) mostly stream weights: every weight byte of a live slot has to
-// cross HBM once whatever the slot's row count.  These kernels are built around that:
+// Under skewed routing a rank's slots split into a few with hundreds of rows and many with
+// a handful, so the two grouped GEMMs of the expert FFN (Sec. 2.1) are partly matrix-bound
+// and partly pure weight streaming: every weight byte of a live slot has to cross HBM once
+// whatever the slot's row count.  What these kernels are built around:
 //
 //   * Expert weights are re-ordered once, outside the forward, into MFMA fragment order
 //     (craft_pack_weights): for each group of output columns and each 16-wide step of the
 //     contraction, the 32 x 16 block that one v_mfma_f32_32x32x16_bf16 consumes as its row
-//     operand is stored as 64 lanes x 16 bytes.  A wave then reads its weights with one
-//     fully coalesced 1 KiB request per MFMA step, straight into registers: no LDS, no
-//     transposition, and each wave of a workgroup streams a different column group, so no
-//     weight byte is requested twice by a workgroup.  For gate/up a group interleaves 16
-//     gate rows with the 16 up rows of the same output columns, which puts gate and up of
-//     one output into the same lane (accumulator elements v and v+8): SwiGLU is applied in
-//     registers.
-//   * The weight stream runs 16 steps (four 64-wide slabs) ahead of the MFMAs in a
-//     statically indexed register ring, which keeps about 16 KiB per wave in flight.
-//   * The activation rows of a tile (up to 128, gathered through the dispatch permutation
+//     operand is stored as 64 lanes x 16 bytes.  A wave reads its weights with one fully
+//     coalesced 1 KiB request per group and step, straight into registers: no LDS, no
+//     transposition, and the waves of a workgroup stream different column groups, so a
+//     workgroup requests no weight byte twice.  For gate/up a group interleaves 16 gate rows
+//     with the 16 up rows of the same output columns, which puts gate and up of one output
+//     into the same lane (accumulator elements v and v+8): SwiGLU is applied in registers.
+//   * One workgroup of four waves per CU, one wave per SIMD, so a wave may use the whole
+//     512-entry register file: a tile is up to 256 activation rows x 8 column groups, each
+//     wave owning two groups x up to eight 32-row fragments (256 fp32 accumulators per
+//     lane).  The large tile is what keeps the L2-to-CU traffic per flop low enough: a
+//     weight fragment loaded into a CU is used against 256 rows, an activation fragment
+//     against 128 (gate/up) or 256 (down) output columns.
+//   * The weight stream runs 4 to 16 steps ahead of the MFMAs in a statically indexed
+//     register ring (deeper for tiles with few rows); the activation rows (gathered through the dispatch permutation
 //     for gate/up) are shared by the four waves through LDS, double buffered, staged through
-//     registers two slabs ahead.  Row fragments beyond the tile's valid rows are skipped
-//     (loads, LDS traffic and MFMAs), so a slot with 20 rows costs a quarter of the matrix
-//     work of a full tile while streaming the same weights.
-//
-// The tile list, its XCD-aware walk and the epilogue layout are those of ffn.hip.
+//     registers two slabs ahead.  The contraction loop has no branch around a memory
+//     operation, so the in-order load counter lets all of that stay in flight.
+//   * Row fragments beyond a tile's valid rows are skipped entirely (loads, LDS traffic,
+//     MFMAs): a slot with 20 rows costs one eighth of the matrix work of a full tile while
+//     streaming the same weights.
+//   * Tiles are listed busiest slot first.  Each workgroup takes one tile by position (the
+//     XCD-aware mapping of ffn_common.h, so tiles sharing weights start together on one
+//     XCD), then pulls further tiles from an atomic counter: the cheap streaming tiles of
+//     the cold slots fill in behind the matrix-bound ones.
 #include "ffn_common.h"
 
 namespace craft {
 namespace {
 
-constexpr int PW = 16;            // weight steps kept in flight per wave
+// Weight steps kept in flight per column group: deep for the streaming-bound tiles with few
+// row fragments, shallower where the accumulators need the registers and each step carries
+// enough MFMA work to cover the latency.
+constexpr int ring_depth(int nxf) { return nxf >= 7 ? 4 : (nxf >= 3 ? 8 : 16); }
+constexpr int NG = 2;             // column groups per wave
 constexpr int XROWB = 64 * 2 + 16;
-constexpr int XSTAGEB = 128 * XROWB;
+constexpr int XSTAGEB = kBM_packed * XROWB;
 
 typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global address space
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 
 // One 64-wide slab U (0..3) of a group of four: prefetch the activation slab two ahead into
-// XL, run the 4 x NXF MFMAs of this slab against LDS stage U&1 while refilling the weight
-// ring four slabs ahead, then put the next slab (already in XS) into the other LDS stage.
-template <int NXF, int U>
+// XL, run the 4 x NG x NXF MFMAs of this slab against LDS stage U&1 while refilling the
+// weight rings PW steps ahead, then put the next slab (already in XS) into the other stage.
+template <int NXF, int U, int PW>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
                                             int frag_off, unsigned char *smem, wstream_t wp,
                                             int64_t wstride, const unsigned short *const (&xp)[NXF],
-                                            bf16x8_t (&wq)[PW], u32x4_t (&XL)[NXF], const u32x4_t (&XS)[NXF],
-                                            f32x16_t (&acc)[NXF]) {
+                                            bf16x8_t (&wq)[NG][PW], u32x4_t (&XL)[NXF],
+                                            const u32x4_t (&XS)[NXF], f32x16_t (&acc)[NG][NXF]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
     const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
 #pragma unroll
@@ -53,14 +66,18 @@ __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, i
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         const int ko = frag_off + kk * 32;
+        const int R = (U * 4 + kk) % PW;           // constant after unrolling
         bf16x8_t xf[NXF];
 #pragma unroll
         for (int g = 0; g < NXF; ++g) xf[g] = *reinterpret_cast<const bf16x8_t *>(xs + g * 32 * XROWB + ko);
 #pragma unroll
-        for (int g = 0; g < NXF; ++g)
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[(U * 4 + kk) % PW], xf[g], acc[g], 0, 0, 0);
-        const int nxt = min(ks * 4 + kk + PW, ksteps - 1);
-        wq[(U * 4 + kk) % PW] = wp[nxt * wstride];
+        for (int n = 0; n < NG; ++n)
+#pragma unroll
+            for (int g = 0; g < NXF; ++g)
+                acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], xf[g], acc[n][g], 0, 0, 0);
+        const int64_t nxt = min(ks * 4 + kk + PW, ksteps - 1) * wstride;
+#pragma unroll
+        for (int n = 0; n < NG; ++n) wq[n][R] = wp[nxt + n * 64];
     }
     unsigned char *xn = smem + ((U + 1) & 1) * XSTAGEB;
 #pragma unroll
@@ -69,24 +86,24 @@ __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, i
     __syncthreads();
 }
 
-// One tile with NXF live 32-row activation fragments.  The contraction loop is free of
-// branches around memory operations (indices past the end are clamped instead; the packed
-// weights are zero there), so the hardware's in-order load counter lets the weight ring and
-// the activation staging really stay in flight.
+// One tile with NXF live 32-row activation fragments.
 template <bool GATEUP, int NXF>
 __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, unsigned char *smem,
                                             int K, int N, int ngroups, int nk4, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
+    constexpr int PW = ring_depth(NXF);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lr = tid >> 3, kc = tid & 7;
     const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
     const int ksteps = nk4 * 16;
-    const int group = t.n0 / GC + wave;
-    const bool wlive = group < ngroups;
+    const int group0 = t.n0 / GC + wave * NG;      // this wave's first column group
     const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
-    // step-major stream: the fragments of all column groups for one step are adjacent
-    wstream_t wp = (wstream_t)wbase + (int64_t)min(group, ngroups - 1) * 64 + lane;
-    const int64_t wstride = (int64_t)ngroups * 64;
+    // step-major stream: the fragments of all column groups for one step are adjacent.
+    // The packed buffer holds a multiple of NG*4 groups (zero padded), so every wave of a
+    // tile has a stream to read even past the last real column.
+    const int groups_padded = (ngroups + NG * 4 - 1) / (NG * 4) * (NG * 4);
+    wstream_t wp = (wstream_t)wbase + (int64_t)group0 * 64 + lane;
+    const int64_t wstride = (int64_t)groups_padded * 64;
     const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
 
     const unsigned short *xp[NXF];
@@ -98,16 +115,20 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
         else xp[i] = xin + (int64_t)(pos - lo_pos) * K;
     }
 
-    f32x16_t acc[NXF];
+    f32x16_t acc[NG][NXF];
 #pragma unroll
-    for (int g = 0; g < NXF; ++g)
+    for (int n = 0; n < NG; ++n)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+        for (int g = 0; g < NXF; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][g][v] = 0.0f;
 
-    bf16x8_t wq[PW];
+    bf16x8_t wq[NG][PW];
     u32x4_t xa[NXF], xb[NXF];
 #pragma unroll
-    for (int j = 0; j < PW; ++j) wq[j] = wp[j * wstride];
+    for (int j = 0; j < PW; ++j)
+#pragma unroll
+        for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
     {
         const int k0 = min(kc * 8, K - 8), k1 = min(64 + kc * 8, K - 8);
 #pragma unroll
@@ -123,58 +144,70 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
 
     const int last_slab = nk4 * 4 - 1;
     for (int ks = 0; ks <= last_slab; ks += 4) {
-        packed_slab<NXF, 0>(ks + 0, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
-        packed_slab<NXF, 1>(ks + 1, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
-        packed_slab<NXF, 2>(ks + 2, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
-        packed_slab<NXF, 3>(ks + 3, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
+        packed_slab<NXF, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
+        packed_slab<NXF, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
+        packed_slab<NXF, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
+        packed_slab<NXF, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
     }
 
     // epilogue.  Accumulator element v of lane l belongs to weight row
     // (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of fragment g.
-    if (!wlive) return;
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
-    const int cbase = group * GC;
 #pragma unroll
-    for (int g = 0; g < NXF; ++g) {
-        const int m = g * 32 + (lane & 31);
-        if (m >= t.rows) continue;
-        unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + m - lo_pos) * N;
-        // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
+    for (int n = 0; n < NG; ++n) {
+        const int cbase = (group0 + n) * GC;
 #pragma unroll
-        for (int vg = 0; vg < (GATEUP ? 2 : 4); ++vg) {
-            const int col = cbase + vg * 8 + (lane >> 5) * 4;
-            if (col >= N) continue;
-            uint32_t h[4];
+        for (int g = 0; g < NXF; ++g) {
+            const int m = g * 32 + (lane & 31);
+            if (m >= t.rows) continue;
+            unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + m - lo_pos) * N;
+            // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                h[c] = GATEUP ? bf16_rne(silu(acc[g][vg * 4 + c]) * acc[g][8 + vg * 4 + c])
-                              : bf16_rne(acc[g][vg * 4 + c]);
-            *reinterpret_cast<uint2 *>(orow + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            for (int vg = 0; vg < (GATEUP ? 2 : 4); ++vg) {
+                const int col = cbase + vg * 8 + (lane >> 5) * 4;
+                if (col >= N) continue;
+                uint32_t h[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    h[c] = GATEUP ? bf16_rne(silu(acc[n][g][vg * 4 + c]) * acc[n][g][8 + vg * 4 + c])
+                                  : bf16_rne(acc[n][g][vg * 4 + c]);
+                *reinterpret_cast<uint2 *>(orow + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            }
         }
     }
 }
 
 template <bool GATEUP>
-__global__ __launch_bounds__(256, 2) void ffn_packed_kernel(FfnArgs a) {
+__global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XSTAGEB];
+    __shared__ int64_t next_item;
     const int K = GATEUP ? a.H : a.I;
     const int N = GATEUP ? a.I : a.H;
     constexpr int GC = GATEUP ? 16 : 32;           // output columns per weight group
-    constexpr int BN = 4 * GC;                     // output columns per tile (one group per wave)
+    constexpr int BN = 4 * NG * GC;                // output columns per tile
     const int ngroups = (N + GC - 1) / GC;
     const int nt = (N + BN - 1) / BN;
     const int nk4 = (K + 255) / 256;               // groups of four 64-wide slabs
     const int64_t total = (int64_t)a.mt_start[a.nslots] * nt;
     const int32_t lo_pos = a.slot_off[a.s_lo];
+    int32_t *counter = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
 
-    for (int64_t w = xcd_major_id(); w < total; w += gridDim.x) {
-        const Tile t = decode_tile(a, w, nt, kBM_bf16, BN);
+    int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
+    while (w < total) {
+        const Tile t = decode_tile(a, w, nt, kBM_packed, BN);
         switch ((t.rows + 31) >> 5) {              // live 32-row fragments of this tile
             case 1: packed_tile<GATEUP, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             case 2: packed_tile<GATEUP, 2>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 3: packed_tile<GATEUP, 3>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            default: packed_tile<GATEUP, 4>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            case 3:
+            case 4: packed_tile<GATEUP, 4>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            case 5:
+            case 6: packed_tile<GATEUP, 6>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            default: packed_tile<GATEUP, 8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
         }
+        if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
+        __syncthreads();
+        w = next_item;
+        __syncthreads();
     }
 }
 
@@ -190,7 +223,7 @@ __global__ void pack_kernel(const unsigned short *wa, const unsigned short *wb, 
     if (c >= nchunks) return;
     const int l = (int)(c & 63);
     const int64_t sg = c >> 6;                   // step-major: chunk = (step * ngroups + group) * 64 + lane
-    const int64_t ngroups = nchunks / 64 / ksteps;
+    const int64_t ngroups = nchunks / 64 / ksteps;   // padded to whole tiles of 8 groups
     const int s = (int)(sg / ngroups);
     const int64_t g = sg % ngroups;
     const int r = l & 31;
@@ -208,10 +241,10 @@ template <bool GATEUP>
 hipError_t launch_packed(const FfnArgs &a, hipStream_t s) {
     if (a.nslots <= 0 || a.max_rows <= 0) return hipSuccess;
     const int N = GATEUP ? a.I : a.H;
-    const int bn = GATEUP ? 64 : 128;
+    const int bn = GATEUP ? 128 : 256;
     const int64_t nt = (N + bn - 1) / bn;
-    const int64_t bound = (a.max_rows / kBM_bf16 + a.nslots) * nt;
-    int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu * 2);
+    const int64_t bound = (a.max_rows / kBM_packed + a.nslots) * nt;
+    int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu);
     grid = std::max<int64_t>(8, (grid + 7) / 8 * 8);
     hipLaunchKernelGGL(ffn_packed_kernel<GATEUP>, dim3((unsigned)grid), dim3(256), 0, s, a);
     return hipGetLastError();
@@ -223,8 +256,8 @@ hipError_t launch_gateup_packed(const FfnArgs &a, hipStream_t s) { return launch
 hipError_t launch_down_packed(const FfnArgs &a, hipStream_t s) { return launch_packed<false>(a, s); }
 
 void packed_sizes(int32_t H, int32_t I, size_t *gateup_bytes, size_t *down_bytes) {
-    const size_t gu_groups = (size_t)(I + 15) / 16, gu_steps = (size_t)(H + 255) / 256 * 16;
-    const size_t dn_groups = (size_t)(H + 31) / 32, dn_steps = (size_t)(I + 255) / 256 * 16;
+    const size_t gu_groups = ((size_t)(I + 15) / 16 + 7) / 8 * 8, gu_steps = (size_t)(H + 255) / 256 * 16;
+    const size_t dn_groups = ((size_t)(H + 31) / 32 + 7) / 8 * 8, dn_steps = (size_t)(I + 255) / 256 * 16;
     *gateup_bytes = gu_groups * gu_steps * 1024;
     *down_bytes = dn_groups * dn_steps * 1024;
 }

@@ -17,7 +17,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- workspace layout of one forward -------------------------------------------------
 struct Layout {
-    size_t ctrl, ids, w, lrank, dest, src, hist, counts, slot_cnt, slot_off, mt_start, act, y, total;
+    size_t ctrl, ids, w, lrank, dest, src, hist, counts, slot_cnt, slot_off, mt_start, order, act, y, total;
     int64_t max_rows, NB;
 };
 
@@ -42,6 +42,7 @@ Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, i
     L.slot_cnt = take((size_t)S * 4);
     L.slot_off = take((size_t)(S + 1) * 4);
     L.mt_start = take((size_t)(nslots + 1) * 4);
+    L.order = take((size_t)(nslots + 1) * 4);
     L.act = take((size_t)L.max_rows * I * es);
     L.y = take((size_t)L.max_rows * H * es);
     L.total = off;
@@ -219,6 +220,8 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     int32_t *slot_cnt = reinterpret_cast<int32_t *>(ws + L.slot_cnt);
     int32_t *slot_off = reinterpret_cast<int32_t *>(ws + L.slot_off);
     int32_t *mt_start = reinterpret_cast<int32_t *>(ws + L.mt_start);
+    int32_t *order = reinterpret_cast<int32_t *>(ws + L.order);
+    const bool packed = a->w_gateup_packed && a->w_down_packed;
     const int32_t *tables = static_cast<const int32_t *>(a->tables);
 
     // 1 route (+ per-block ranks and counts); user copies of ids / weights are written by the
@@ -234,8 +237,8 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     {
         ScopedEvent ev(CRAFT_K_SCAN, s);
         ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi,
-                    a->dtype == CRAFT_BF16 ? kBM_bf16 : kBM_f32, L.max_rows,
-                    counts, slot_cnt, slot_off, mt_start, ctrl,
+                    a->dtype == CRAFT_BF16 ? (packed ? kBM_packed : kBM_bf16) : kBM_f32, L.max_rows,
+                    counts, slot_cnt, slot_off, mt_start, order, ctrl,
                     a->counts, a->slot_cnt, a->slot_off};
         if (launch_scan(sa, s) != hipSuccess) return CRAFT_EHIP;
     }
@@ -246,11 +249,10 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
         if (launch_dispatch(da, s) != hipSuccess) return CRAFT_EHIP;
     }
     // 4 grouped FFN
-    FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, ctrl,
+    FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, order, ctrl,
                a->w_gate, a->w_up, a->w_down, a->w_gateup_packed, a->w_down_packed,
                ws + L.act, ws + L.y, L.max_rows, cached_num_cu()};
     if (a->T > 0) {
-        const bool packed = a->w_gateup_packed && a->w_down_packed;
         {
             ScopedEvent ev(CRAFT_K_GATEUP, s);
             if ((packed ? launch_gateup_packed(fa, s) : launch_gateup(fa, s)) != hipSuccess)

@@ -15,10 +15,13 @@ namespace craft {
 constexpr int kTokPerBlock = 32;
 
 // Control words at the start of the workspace.
-enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3, CTRL_WORDS = 16 };
+enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
+       CTRL_WORK_GATEUP = 4, CTRL_WORK_DOWN = 5,   // dynamic tile counters of the two GEMMs
+       CTRL_WORDS = 16 };
 
 // Rows per row-tile of the grouped GEMMs (the unit the tile table counts in).
-constexpr int kBM_bf16 = 128;
+constexpr int kBM_bf16 = 128;      // LDS-staged bf16 kernels (row-major weights)
+constexpr int kBM_packed = 256;    // weight-streaming bf16 kernels (packed weights)
 constexpr int kBM_f32 = 32;
 
 struct RouteArgs {
@@ -43,7 +46,8 @@ struct ScanArgs {
     int32_t *counts;          // [E]
     int32_t *slot_cnt;        // [S]
     int32_t *slot_off;        // [S+1]
-    int32_t *mt_start;        // [s_hi - s_lo + 1]
+    int32_t *mt_start;        // [s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot first
+    int32_t *order;           // [s_hi - s_lo] local slot at each position of that order
     int32_t *ctrl;
     int32_t *user_counts, *user_slot_cnt, *user_slot_off;   // optional copies
 };
@@ -70,7 +74,8 @@ struct FfnArgs {
     const int32_t *src;            // [A]
     const int32_t *slot_off;       // [S+1]
     const int32_t *mt_start;       // [nslots+1]
-    const int32_t *ctrl;
+    const int32_t *order;          // [nslots]
+    int32_t *ctrl;
     const void *const *w_gate, *const *w_up, *const *w_down;   // row-major weights per slot
     const void *const *wp_gateup, *const *wp_down;             // fragment-packed weights per slot
     void *act;                     // [max_rows][I] SwiGLU activations

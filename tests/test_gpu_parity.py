@@ -196,9 +196,9 @@ def test_packed_weights_layout(torch_cuda):
                         out[s, gi, l] = src[k0:k0 + 8]
         return out.reshape(-1)
 
-    gu = expect((I + 15) // 16, (H + 255) // 256 * 16,
+    gu = expect(((I + 15) // 16 + 7) // 8 * 8, (H + 255) // 256 * 16,
                 lambda gi, r: (Wg if r < 16 else Wu)[16 * gi + (r & 15)] if 16 * gi + (r & 15) < I else None, H)
-    dn = expect((H + 31) // 32, (I + 255) // 256 * 16,
+    dn = expect(((H + 31) // 32 + 7) // 8 * 8, (I + 255) // 256 * 16,
                 lambda gi, r: Wd[32 * gi + r] if 32 * gi + r < H else None, I)
     assert np.array_equal(pgu, gu) and np.array_equal(pdn, dn)
 
