@@ -11,23 +11,30 @@ from paper_2603_28768_amd import binding, synth
 
 
 class Case:
-    def __init__(self, cfg: synth.LayerConfig, rank=None):
+    def __init__(self, cfg: synth.LayerConfig, plan=None, layer: int = 0, pop=None):
+        """Without `plan`: a one-layer plan is made from this config's profiling batches.
+        With `plan` (and the layer's popularity `pop`): the evaluation batch of layer
+        `layer` of a multi-layer plan made elsewhere."""
         self.cfg = cfg
-        self.pop = synth.layer_popularity(cfg)
-        W = np.zeros((cfg.profile_batches, 1, cfg.E), dtype=np.int64)
-        for b in range(cfg.profile_batches):
-            ids, _ = oracle.route(synth.router_logits(cfg, self.pop, "profile", b), cfg.k)
-            W[b, 0] = oracle.expert_load(ids[None], cfg.E, max(cfg.T, 1))[0, 0]
-        self.W = W
-        self.plan = binding.Plan(W, cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
-        ref = po.make_plan(W.tolist(), cfg.D, None, cfg.replica_slots)
-        self.layer = self.plan.layer(0)
-        assert self.layer["slot_expert"].tolist() == ref["layers"][0]["slot_expert"]
-        assert self.layer["rank_slot_off"].tolist() == ref["layers"][0]["rank_slot_off"]
+        self.layer_index = layer
+        self.pop = synth.layer_popularity(cfg, layer) if pop is None else pop
+        if plan is None:
+            W = np.zeros((cfg.profile_batches, 1, cfg.E), dtype=np.int64)
+            for b in range(cfg.profile_batches):
+                ids, _ = oracle.route(synth.router_logits(cfg, self.pop, "profile", b), cfg.k)
+                W[b, 0] = oracle.expert_load(ids[None], cfg.E, max(cfg.T, 1))[0, 0]
+            self.W = W
+            plan = binding.Plan(W, cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
+            ref = po.make_plan(W.tolist(), cfg.D, None, cfg.replica_slots)
+            lay = plan.layer(0)
+            assert lay["slot_expert"].tolist() == ref["layers"][0]["slot_expert"]
+            assert lay["rank_slot_off"].tolist() == ref["layers"][0]["rank_slot_off"]
+        self.plan = plan
+        self.layer = self.plan.layer(layer)
         self.slot_expert = self.layer["slot_expert"]
         self.rank_slot_off = self.layer["rank_slot_off"]
-        self.logits = synth.router_logits(cfg, self.pop, "eval")
-        self.x = synth.activations(cfg)
+        self.logits = synth.router_logits(cfg, self.pop, "eval", layer=layer)
+        self.x = synth.activations(cfg, layer=layer)
         self.ids, self.w = oracle.route(self.logits, cfg.k)
         self.dest, self.src, self.slot_cnt, self.slot_off = oracle.dispatch(
             self.ids, cfg.E, self.slot_expert)
@@ -37,7 +44,7 @@ class Case:
 
     def weights_of(self, e: int):
         if e not in self._wcache:
-            self._wcache[e] = synth.expert_weights(self.cfg, e)
+            self._wcache[e] = synth.expert_weights(self.cfg, e, self.layer_index)
         return self._wcache[e]
 
     def rank_slots(self, rank: int):
@@ -64,7 +71,7 @@ class Case:
             wg.append(g); wu.append(u); wd.append(d)
             if packed:
                 pk.append(pack_cache[e])
-        fwd = binding.RankForward(self.plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
+        fwd = binding.RankForward(self.plan, self.layer_index, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                                   wg, wu, wd, True, max_rows, device, want_debug_outputs=debug,
                                   packed=pk if packed else None)
         x = binding.to_device(self.x, cfg.dtype, device)
