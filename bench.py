@@ -132,12 +132,57 @@ def cpu_baseline(cfg, st, budget_s=15.0):
                 est_seconds_per_step=est)
 
 
+def bench_trace_load(args):
+    """Secondary workload: craft_expert_load over the multi-layer stack's routing trace
+    (58 layers x 2^20 tokens x top-8 of 256 experts, int32, 1.95 GB), resident in HBM.
+    The trace is drawn on the device (Gumbel top-k over each layer's Zipf popularity)."""
+    import torch
+    from paper_2603_28768_amd import binding, synth
+    L, E, k, T, bt = 58, 256, 8, 1 << 20, 4096
+    s = synth.trace_layer_exponents(L, 5)
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 5)
+    ids = torch.empty((L, T, k), dtype=torch.int32, device="cuda")
+    for l in range(L):
+        logp = torch.from_numpy(np.log(synth.popularity(E, s[l], 5, l))).float().cuda()
+        for c in range(0, T, 1 << 18):
+            u = torch.rand((1 << 18, E), generator=g, device="cuda").clamp_(1e-20, 1.0)
+            gum = logp - torch.log(-torch.log(u))
+            ids[l, c:c + (1 << 18)] = torch.topk(gum, k, dim=1).indices.to(torch.int32)
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        counts = binding.expert_load(ids, E, bt)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for _ in range(args.steps):
+        counts = binding.expert_load(ids, E, bt)
+    ev[1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = ev[0].elapsed_time(ev[1]) / args.steps         # kernels run on torch's current stream
+    assert int(counts.sum()) == L * T * k
+    nbytes = ids.numel() * 4 + counts.numel() * 8
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    out = dict(metric="expert-load histogram assignments/s on 1 GPU", value=ids.numel() / (dt / args.steps),
+               unit="assignments/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=dt / args.steps * 1e3, higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="int32", data="synthetic",
+               config=dict(workload=f"routing trace {L} layers x {T} tokens x top-{k} of {E} experts, "
+                                    f"Zipf s in [0.6,1.6], batches of {bt} tokens"),
+               roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                             frac=gbs / HBM_PEAK_GBS, traffic=None, kernel="expert_load_kernel",
+                             avg_ms=ms, algorithmic_bytes=nbytes))
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="qwen3", help="tiny | qwen3 | dsv3 | kimi | dsv3_long")
+    ap.add_argument("--config", default="qwen3",
+                    help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unpacked", action="store_true",
                     help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
@@ -153,6 +198,8 @@ def main():
     from paper_2603_28768_amd import binding, synth
     binding.lib()                       # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.config == "trace_load":
+        return bench_trace_load(args)
     cfg = synth.CONFIGS[args.config]
     st = setup(cfg, packed=not args.unpacked)
     fwd, x, logits = st["fwd"], st["x"], st["logits"]

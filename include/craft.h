@@ -77,10 +77,8 @@ craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, in
  *   the estimated maximum rank load per byte, until no further replica fits the budget.
  *   The estimate is Alg. 1's model on the aggregated load: a copy of expert e carries
  *   floor(W_s[e] / copies[e]) and a rank's load is the sum over the copies it holds.
- * objective 1: the paper's own pipeline -- Alg. 1 replays every batch for replica counts
- *   1,2,4,..,D to get per-layer balancedness gains, Alg. 2 picks one count per layer by
- *   dynamic programming so that the counts sum to budget_bytes / bytes_per_replica
- *   (all layers must then share one replica size).
+ * objective 1: reserved for the paper's own pipeline (Alg. 1 replay of every batch for replica
+ *   counts 1,2,4,..,D, then Alg. 2's dynamic program).  Not implemented: CRAFT_EINVAL.
  */
 typedef struct craft_plan craft_plan_t;
 
@@ -93,7 +91,7 @@ typedef struct {
     const int64_t *load;       /* HOST [B][L][E] token counts, all >= 0 */
     const int64_t *bytes_per_replica; /* HOST [L], each > 0; NULL = 1 everywhere */
     int64_t budget_bytes;      /* total over all layers and ranks, >= 0 */
-    int32_t objective;         /* 0 or 1, see above */
+    int32_t objective;         /* 0, see above */
 } craft_plan_params;
 
 craft_status craft_plan(const craft_plan_params *params, craft_plan_t **out);
