@@ -176,13 +176,35 @@ def bench_trace_load(args):
     print(json.dumps(out), flush=True)
 
 
+def copy_calibration(args):
+    """A plain 256 MiB device-to-device copy: the known-size kernel against which the
+    FETCH_SIZE / WRITE_SIZE counters are scaled, and the box's own copy bandwidth."""
+    import torch
+    n = 256 << 20
+    a = torch.ones(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(args.steps):
+        b.copy_(a)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    print(json.dumps(dict(metric="device copy GB/s (read+write)", value=2 * n / (ms * 1e-3) / 1e9,
+                          unit="GB/s", bytes_read=n, bytes_written=n, ms_per_step=ms)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="qwen3",
-                    help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only)")
+                    help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only) | "
+                         "copy_calib (plain copy for counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unpacked", action="store_true",
                     help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
@@ -200,6 +222,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.config == "trace_load":
         return bench_trace_load(args)
+    if args.config == "copy_calib":
+        return copy_calibration(args)
     cfg = synth.CONFIGS[args.config]
     st = setup(cfg, packed=not args.unpacked)
     fwd, x, logits = st["fwd"], st["x"], st["logits"]
