@@ -40,7 +40,7 @@ namespace {
 // Weight steps kept in flight per column group: deep for the streaming-bound tiles with few
 // row fragments, shallower where the accumulators need the registers and each step carries
 // enough MFMA work to cover the latency.
-constexpr int ring_depth(int nxf) { return nxf >= 7 ? 4 : (nxf >= 3 ? 8 : 16); }
+constexpr int ring_depth(int nxf) { return nxf >= 3 ? 8 : 16; }
 constexpr int NG = 2;             // column groups per wave
 constexpr int XROWB = 64 * 2 + 16;
 constexpr int XSTAGEB = kBM_packed * XROWB;
@@ -49,41 +49,65 @@ typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 
-// One 64-wide slab U (0..3) of a group of four: prefetch the activation slab two ahead into
-// XL, run the 4 x NG x NXF MFMAs of this slab against LDS stage U&1 while refilling the
-// weight rings PW steps ahead, then put the next slab (already in XS) into the other stage.
+// One 16-wide contraction step of NG x NXF MFMAs.  A wave is alone on its SIMD, so whatever
+// it issues between two MFMAs delays the second one unless it fits into the 32 cycles the
+// first one keeps the matrix pipeline busy: memory operations are therefore dealt out one or
+// two per MFMA, and a scheduling barrier after each MFMA pins that order.
+//   MFMA j < NXF        : + LDS read of fragment j of the FOLLOWING step into XN (a whole step
+//                         of matrix work covers its latency; this step runs on XC)
+//   MFMA NXF + i        : + (PHASE 0/1, the first two steps of a slab) activation row chunk i
+//                         of the next slab goes from XR to LDS stage `nxt`, and the same
+//                         registers are requested again for the slab after it
+//   MFMA NXF, 2 NXF - 1 : + refill of the weight ring slot each column group has just used
+template <int NXF, int R, int PW, int PHASE>
+__device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, wstream_t wp,
+                                            int64_t wstride, bf16x8_t (&wq)[NG][PW],
+                                            const bf16x8_t (&XC)[NXF], bf16x8_t (&XN)[NXF],
+                                            f32x16_t (&acc)[NG][NXF], unsigned char *xstage,
+                                            u32x4_t (&XR)[NXF], const unsigned short *const (&xp)[NXF],
+                                            int koff) {
+    constexpr int HALF = (NXF + 1) / 2;
+    const int64_t nxt = min(step + PW, ksteps - 1) * wstride;
+#pragma unroll
+    for (int n = 0; n < NG; ++n)
+#pragma unroll
+        for (int g = 0; g < NXF; ++g) {
+            acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], XC[g], acc[n][g], 0, 0, 0);
+            if (n == 0) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
+            if (n == 1 && PHASE < 2) {
+                const int i = PHASE * HALF + g;
+                if (g < HALF && i < NXF) {
+                    *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
+                    XR[i] = *(xchunk_t)(xp[i] + koff);
+                }
+            }
+            if (g == NXF - 1) wq[n][R] = wp[nxt + n * 64];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
+// One 64-wide slab U (0..3) of a group of four.  On entry LDS stage `cur` holds this slab,
+// XR the next slab (in registers, requested one slab ago) and X0 the fragments of this
+// slab's first step.  During the first two steps XR goes into stage `nxt` and the slab two
+// ahead is requested from global memory into the same registers; the last step already
+// fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
+// enough: a stage is rewritten a full slab after its last reader has passed a barrier.
 template <int NXF, int U, int PW>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
-                                            int frag_off, unsigned char *smem, wstream_t wp,
-                                            int64_t wstride, const unsigned short *const (&xp)[NXF],
-                                            bf16x8_t (&wq)[NG][PW], u32x4_t (&XL)[NXF],
-                                            const u32x4_t (&XS)[NXF], f32x16_t (&acc)[NG][NXF]) {
+                                            const unsigned char *cur, unsigned char *nxt, int frag_off,
+                                            wstream_t wp, int64_t wstride,
+                                            const unsigned short *const (&xp)[NXF], bf16x8_t (&wq)[NG][PW],
+                                            u32x4_t (&XR)[NXF], bf16x8_t (&X0)[NXF], bf16x8_t (&X1)[NXF],
+                                            f32x16_t (&acc)[NG][NXF]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
     const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
-#pragma unroll
-    for (int i = 0; i < NXF; ++i) XL[i] = *(xchunk_t)(xp[i] + koff);
-    const unsigned char *xs = smem + (U & 1) * XSTAGEB;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int ko = frag_off + kk * 32;
-        const int R = (U * 4 + kk) % PW;           // constant after unrolling
-        bf16x8_t xf[NXF];
-#pragma unroll
-        for (int g = 0; g < NXF; ++g) xf[g] = *reinterpret_cast<const bf16x8_t *>(xs + g * 32 * XROWB + ko);
-#pragma unroll
-        for (int n = 0; n < NG; ++n)
-#pragma unroll
-            for (int g = 0; g < NXF; ++g)
-                acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], xf[g], acc[n][g], 0, 0, 0);
-        const int64_t nxt = min(ks * 4 + kk + PW, ksteps - 1) * wstride;
-#pragma unroll
-        for (int n = 0; n < NG; ++n) wq[n][R] = wp[nxt + n * 64];
-    }
-    unsigned char *xn = smem + ((U + 1) & 1) * XSTAGEB;
-#pragma unroll
-    for (int i = 0; i < NXF; ++i)
-        *reinterpret_cast<u32x4_t *>(xn + (lr + 32 * i) * XROWB + kc * 16) = XS[i];
+    unsigned char *xstage = nxt + lr * XROWB + kc * 16;
+    const unsigned char *xs = cur + frag_off;
+    packed_step<NXF, (U * 4 + 0) % PW, PW, 0>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, (U * 4 + 1) % PW, PW, 1>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
     __syncthreads();
+    packed_step<NXF, (U * 4 + 2) % PW, PW, 2>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, (U * 4 + 3) % PW, PW, 2>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
 }
 
 // One tile with NXF live 32-row activation fragments.
@@ -123,31 +147,49 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[n][g][v] = 0.0f;
 
+    // Request order: half the weight ring, the first two activation slabs, the other half of
+    // the ring.  The second slab is then followed by as many weight requests as in the loop,
+    // so the in-order load counter need not be drained when the loop is entered.
     bf16x8_t wq[NG][PW];
-    u32x4_t xa[NXF], xb[NXF];
-#pragma unroll
-    for (int j = 0; j < PW; ++j)
-#pragma unroll
-        for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
+    u32x4_t xr[NXF];
     {
+        u32x4_t xfirst[NXF];
+#pragma unroll
+        for (int j = 0; j < PW / 2; ++j)
+#pragma unroll
+            for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
         const int k0 = min(kc * 8, K - 8), k1 = min(64 + kc * 8, K - 8);
 #pragma unroll
-        for (int i = 0; i < NXF; ++i) {
-            xa[i] = *(xchunk_t)(xp[i] + k0);
-            xb[i] = *(xchunk_t)(xp[i] + k1);
-        }
+        for (int i = 0; i < NXF; ++i) xfirst[i] = *(xchunk_t)(xp[i] + k0);
+#pragma unroll
+        for (int i = 0; i < NXF; ++i) xr[i] = *(xchunk_t)(xp[i] + k1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = PW / 2; j < PW; ++j)
+#pragma unroll
+            for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NXF; ++i)
-            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xa[i];
+            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xfirst[i];
     }
     __syncthreads();
 
+    bf16x8_t x0[NXF], x1[NXF];
+#pragma unroll
+    for (int g = 0; g < NXF; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 32 * XROWB);
+
     const int last_slab = nk4 * 4 - 1;
+    int st = 0;                                    // LDS stage of the current slab
     for (int ks = 0; ks <= last_slab; ks += 4) {
-        packed_slab<NXF, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
-        packed_slab<NXF, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
-        packed_slab<NXF, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xa, xb, acc);
-        packed_slab<NXF, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, frag_off, smem, wp, wstride, xp, wq, xb, xa, acc);
+        unsigned char *s0 = smem + st * XSTAGEB;
+        unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
+        unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
+        packed_slab<NXF, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        st = (st + 1) % 3;
     }
 
     // epilogue.  Accumulator element v of lane l belongs to weight row
@@ -179,8 +221,11 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
 
 template <bool GATEUP>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * XSTAGEB];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
     __shared__ int64_t next_item;
+    __shared__ TileTables tt;
+    const bool small = a.nslots <= TileTables::kMaxSlots;
+    if (small) load_tile_tables(a, tt);
     const int K = GATEUP ? a.H : a.I;
     const int N = GATEUP ? a.I : a.H;
     constexpr int GC = GATEUP ? 16 : 32;           // output columns per weight group
@@ -194,7 +239,7 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
 
     int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
-        const Tile t = decode_tile(a, w, nt, kBM_packed, BN);
+        const Tile t = small ? decode_tile(a, tt, w, nt, kBM_packed, BN) : decode_tile(a, w, nt, kBM_packed, BN);
         switch ((t.rows + 31) >> 5) {              // live 32-row fragments of this tile
             case 1: packed_tile<GATEUP, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             case 2: packed_tile<GATEUP, 2>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
