@@ -197,6 +197,36 @@ def copy_calibration(args):
                           unit="GB/s", bytes_read=n, bytes_written=n, ms_per_step=ms)), flush=True)
 
 
+def plan_curves(args):
+    """Balancedness against replica budget on the stack-shaped loads (58 layers x 256
+    experts, 32 ranks, per-layer Zipf exponents in [0.6, 1.6]) for the three allocation rules
+    of craft_plan: the paper's pipeline (Alg. 1 + Alg. 2), the unit greedy and even spreading
+    (R = L is uniform replication).  Host only; prints one JSON line."""
+    from paper_2603_28768_amd import binding, synth
+    L, E, D, B = 58, 256, 32, 4
+    s = synth.trace_layer_exponents(L, 5)
+    g = np.random.default_rng(5)
+    W = np.stack([[g.multinomial(8 * 4096, synth.popularity(E, s[l], 5, l)) for l in range(L)]
+                  for _ in range(B)]).astype(np.int64)
+
+    def mean_bal(p):
+        return float(np.mean([p.layer(l)["est_balancedness"] for l in range(L)]))
+
+    rows = []
+    for R in (0, 1, 2, 4, 8, 16, 32, 58):
+        row = {"R": R}
+        for name, obj in (("paper", 1), ("greedy", 0), ("spread", 2)):
+            t0 = time.perf_counter()
+            p = binding.Plan(W, D, R * D, objective=obj)
+            row[name] = round(mean_bal(p), 4)
+            row[name + "_ms"] = round((time.perf_counter() - t0) * 1e3, 2)
+        rows.append(row)
+        log(str(row))
+    auto = binding.Plan(W, D, L * D, objective=1, auto_r=True).benefit()["auto_R"]
+    print(json.dumps({"metric": "mean estimated balancedness vs replication factor", "L": L, "E": E,
+                      "D": D, "profiling_batches": B, "curves": rows, "auto_R": int(auto)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,7 +234,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="qwen3",
                     help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only) | "
-                         "copy_calib (plain copy for counter calibration)")
+                         "copy_calib (plain copy for counter calibration) | "
+                         "plan_curves (host only: balancedness vs budget for the three planners)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unpacked", action="store_true",
                     help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
@@ -216,9 +247,11 @@ def main():
             "--gpus above 1 is not part of this build")
         sys.exit(2)
 
-    import torch
     from paper_2603_28768_amd import binding, synth
     binding.lib()                       # fail loudly if the HIP library is missing
+    if args.config == "plan_curves":
+        return plan_curves(args)
+    import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.config == "trace_load":
         return bench_trace_load(args)

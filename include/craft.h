@@ -77,8 +77,20 @@ craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, in
  *   the estimated maximum rank load per byte, until no further replica fits the budget.
  *   The estimate is Alg. 1's model on the aggregated load: a copy of expert e carries
  *   floor(W_s[e] / copies[e]) and a rank's load is the sum over the copies it holds.
- * objective 1: reserved for the paper's own pipeline (Alg. 1 replay of every batch for replica
- *   counts 1,2,4,..,D, then Alg. 2's dynamic program).  Not implemented: CRAFT_EINVAL.
+ * objective 1: the paper's own pipeline (Sec. 4.2.1).  Alg. 1: for r = 0 and r = 1,2,4,..<=D
+ *   every layer is placed on the summed loads with r replicas and every profiling batch is
+ *   replayed under that placement (a copy carries floor(W[b][l][e] / copies[e])); the gain
+ *   of r is the mean over batches of (average / maximum rank load) minus the same at r = 0.
+ *   Alg. 2: one count per layer from {0,1,2,4,..}, summing exactly to the replica total,
+ *   with the largest total gain (ties: no replica, then the smaller count).  The total is
+ *   budget_bytes / bytes_per_replica, capped at what the counts can hold; a total no
+ *   selection reaches falls back to the next lower reachable one.  With auto_r != 0 the
+ *   total is R * D for the R >= 1, R * D <= budget, with the highest total gain per replica
+ *   (step 2's automatic mode; ties: smaller R).
+ * objective 2: the comparison plans of Sec. 5: every layer gets floor(budget / L) replicas
+ *   (0 = placement only; budget L * D = uniform replication, one replica per layer per rank).
+ * Objectives 1 and 2 count replicas: bytes_per_replica must be NULL or equal in all layers
+ * (CRAFT_EINVAL otherwise).
  */
 typedef struct craft_plan craft_plan_t;
 
@@ -91,7 +103,8 @@ typedef struct {
     const int64_t *load;       /* HOST [B][L][E] token counts, all >= 0 */
     const int64_t *bytes_per_replica; /* HOST [L], each > 0; NULL = 1 everywhere */
     int64_t budget_bytes;      /* total over all layers and ranks, >= 0 */
-    int32_t objective;         /* 0, see above */
+    int32_t objective;         /* 0, 1 or 2, see above */
+    int32_t auto_r;            /* objective 1 only: choose the replication factor (see above) */
 } craft_plan_params;
 
 craft_status craft_plan(const craft_plan_params *params, craft_plan_t **out);
@@ -123,6 +136,15 @@ craft_status craft_plan_layer_tables(const craft_plan_t *plan, int32_t layer, in
  * layers[i].  Returns the number of steps in *n; copies min(*n, cap) entries. */
 craft_status craft_plan_greedy_order(const craft_plan_t *plan, int32_t *layers, int64_t cap,
                                      int64_t *n);
+
+/* Objective 1's benefit matrix (Alg. 1 output) and what the allocation made of it; any
+ * pointer may be NULL.  n_counts = K candidate counts; counts HOST [K] (1, 2, 4, ..);
+ * base HOST [L] = mean placement-only balancedness; gain HOST [K][L]; total_gain = sum of
+ * the gains of the counts Alg. 2 chose; auto_R = the replication factor the automatic
+ * mode picked (0 when it was off).  K is 0 for plans of other objectives. */
+craft_status craft_plan_benefit(const craft_plan_t *plan, int32_t *n_counts, int32_t *counts,
+                                double *base, double *gain, double *total_gain,
+                                int32_t *auto_R);
 
 /* Rows each rank would execute for a batch with the given per-expert token counts under
  * the plan's dispatch rule (the i-th token of expert e goes to copy i mod copies[e]).

@@ -23,6 +23,16 @@ Steps and where they come from:
   capacity_assignment   Alg. 3, interleaved per-layer per-rank expert capacity.
   make_plan             Sec. 4.2 workflow, steps 3-5, then per-layer reporting
                         (balancedness = average / maximum rank load, Sec. 3.1).
+  replication_benefit   Alg. 1 in full: every profiling batch replayed under the
+                        placement for each candidate replica count; per-layer mean
+                        balancedness gain over placement-only.
+  choose_replication_factor  Sec. 4.2.1 step 2: the R with the highest balancedness
+                        gain per replica.
+  make_plan_paper       the paper's own pipeline: Alg. 1 -> (R) -> Alg. 2 -> Alg. 3 ->
+                        placement.
+  make_plan_uniform     the comparison plans of Sec. 5: placement only (n = 0) and the
+                        same number of replicas in every layer (n = D is the uniform
+                        replication baseline).
 """
 from __future__ import annotations
 
@@ -254,6 +264,149 @@ def make_plan(W, D: int, bytes_per_replica: Optional[Sequence[int]], budget: int
     return dict(L=L, E=E, D=D, x=x, order=order, layers=layers, total_replicas=total,
                 replication_factor=total / D,
                 memory_saving_vs_uniform=(L * D / total) if total else float("inf"))
+
+
+def geometric_counts(D: int, E: int) -> List[int]:
+    """Sec. 4.2.1 step 1: the candidate replica counts 1, 2, 4, ... up to D (and never
+    more than a layer can take: every expert on every rank, E * (D - 1) replicas)."""
+    out, r = [], 1
+    while r <= D and r <= E * (D - 1):
+        out.append(r)
+        r *= 2
+    return out
+
+
+def replication_benefit(W, D: int, counts: Optional[Sequence[int]] = None
+                        ) -> Tuple[List[int], List[float], Dict[int, List[float]]]:
+    """Alg. 1.  W[b][l][e] integer loads.  Returns (counts, base[l], T[r][l]).
+
+    For r = 0 and every candidate count r the layer is placed once on the loads
+    summed over batches (r replicas by expert_copies, capacities floor/ceil of
+    (E + r) / D with the extras on the lowest ranks, greedy placement).  Every batch
+    is then replayed under that placement: each copy of expert e carries
+    floor(W[b][l][e] / copies[e]) on the rank that holds it, and the batch scores
+    (average rank load) / (maximum rank load); a batch that sends nothing to the
+    layer scores 1.  base[l] is the mean score over batches at r = 0 and
+    T[r][l] the mean score at r minus base[l].  (The listing's single `base` is read
+    per layer: it is assigned from BAL[l].)  Arithmetic: integer loads; one double
+    division of the load sum by D, one by the maximum, a running double sum over
+    batches in order, one division by B, one subtraction.
+    """
+    Ws = aggregate_load(W)
+    B, L, E = len(W), len(Ws), len(Ws[0])
+    counts = geometric_counts(D, E) if counts is None else [int(r) for r in counts]
+    base = [0.0] * L
+    T: Dict[int, List[float]] = {}
+    for r in [0] + list(counts):
+        mean = [0.0] * L
+        for l in range(L):
+            c = expert_copies(Ws[l], r, D)
+            held, _ = placement(Ws[l], c, canonical_capacities(E + r, D))
+            bal = 0.0
+            for b in range(B):
+                G = [0] * D
+                for g in range(D):
+                    for e, _q in held[g]:
+                        G[g] += int(W[b][l][e]) // c[e]
+                mx = max(G)
+                bal += 1.0 if mx == 0 else (sum(G) / D) / mx
+            mean[l] = bal / B
+        if r == 0:
+            base = mean
+        else:
+            T[r] = [mean[l] - base[l] for l in range(L)]
+    return list(counts), base, T
+
+
+def mckp_table(Tmap: Dict[int, Sequence[float]], C: int):
+    """The value table of Alg. 2 for every capacity 0..C at once: best[c] = the maximum
+    total gain of a selection that sums to exactly c (None when no selection does)."""
+    keys = sorted(Tmap.keys())
+    L = len(Tmap[keys[0]])
+    prev: List[Optional[float]] = [None] * (C + 1)
+    prev[0] = 0.0
+    for l in range(1, L + 1):
+        cur: List[Optional[float]] = [None] * (C + 1)
+        for c in range(C + 1):
+            cur[c] = prev[c]
+            for r in keys:
+                if c >= r and prev[c - r] is not None:
+                    cand = prev[c - r] + Tmap[r][l - 1]
+                    if cur[c] is None or cand > cur[c]:
+                        cur[c] = cand
+        prev = cur
+    return prev
+
+
+def choose_replication_factor(Tmap: Dict[int, Sequence[float]], D: int, R_max: int) -> int:
+    """Sec. 4.2.1 step 2, automatic mode: the replication factor R in 1..R_max whose best
+    allocation of R * D replicas has the highest total gain per replica (exact-sum
+    allocations as in Alg. 2; an R no selection sums to is skipped; ties keep the
+    smaller R).  Returns 0 when no R in range is reachable."""
+    best_tab = mckp_table(Tmap, R_max * D)
+    best_R, best_v = 0, 0.0
+    for R in range(1, R_max + 1):
+        v = best_tab[R * D]
+        if v is None:
+            continue
+        per = v / (R * D)
+        if best_R == 0 or per > best_v:
+            best_R, best_v = R, per
+    return best_R
+
+
+def _finish_plan(Ws, D: int, x: Sequence[int], extra: dict) -> dict:
+    L, E = len(Ws), len(Ws[0])
+    A = capacity_assignment(D, [E + x[l] for l in range(L)])
+    layers = []
+    for l in range(L):
+        c = expert_copies(Ws[l], x[l], D)
+        held, load = placement(Ws[l], c, A[l])
+        slot_expert, off = layer_tables(held)
+        mx = max(load)
+        bal = 1.0 if mx == 0 else (sum(load) / D) / mx
+        layers.append(dict(n_replicas=x[l], copies=c, slot_expert=slot_expert,
+                           rank_slot_off=off, capacity=A[l], rank_load=load,
+                           est_max_rank_load=mx, est_balancedness=bal))
+    total = sum(x)
+    out = dict(L=L, E=E, D=D, x=list(x), order=[], layers=layers, total_replicas=total,
+               replication_factor=total / D,
+               memory_saving_vs_uniform=(L * D / total) if total else float("inf"))
+    out.update(extra)
+    return out
+
+
+def make_plan_paper(W, D: int, budget_replicas: int, auto_R: bool = False) -> dict:
+    """The paper's pipeline (Sec. 4.2.1): benefit matrix by Alg. 1, the replica total
+    (given, or R * D with R from choose_replication_factor, R * D <= budget), the
+    per-layer counts by Alg. 2, then Alg. 3 and the greedy placement.
+
+    Alg. 2 needs a selection that sums to the total exactly; when none does (a total
+    no combination of 0, 1, 2, 4, .. per layer reaches) the largest reachable total
+    below it is used."""
+    Ws = aggregate_load(W)
+    L = len(Ws)
+    counts, base, T = replication_benefit(W, D)
+    if not counts:                       # a single rank: nothing to replicate onto
+        return _finish_plan(Ws, D, [0] * L, dict(benefit_counts=[], benefit_base=base,
+                                                 benefit={}, total_gain=0.0))
+    cap = min(int(budget_replicas), L * max(counts))
+    if auto_R:
+        R = choose_replication_factor(T, D, cap // D)
+        cap = R * D
+    tab = mckp_table(T, cap)
+    while tab[cap] is None:
+        cap -= 1
+    x = mckp_allocation(T, cap) if cap > 0 else [0] * L
+    return _finish_plan(Ws, D, x, dict(benefit_counts=counts, benefit_base=base, benefit=T,
+                                       total_gain=tab[cap]))
+
+
+def make_plan_uniform(W, D: int, n: int) -> dict:
+    """Comparison plans (Sec. 5 setups): n = 0 is placement only, n = D the uniform
+    replication baseline (one replica per layer per rank); every layer gets n."""
+    Ws = aggregate_load(W)
+    return _finish_plan(Ws, D, [int(n)] * len(Ws), {})
 
 
 def realized_rank_rows(slot_cnt: Sequence[int], rank_slot_off: Sequence[int]) -> List[int]:

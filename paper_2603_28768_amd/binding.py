@@ -25,7 +25,7 @@ P = ctypes.POINTER
 class PlanParams(ctypes.Structure):
     _fields_ = [("L", c_i32), ("E", c_i32), ("D", c_i32), ("gpus_per_node", c_i32), ("B", c_i64),
                 ("load", c_vp), ("bytes_per_replica", c_vp), ("budget_bytes", c_i64),
-                ("objective", c_i32)]
+                ("objective", c_i32), ("auto_r", c_i32)]
 
 
 class FwdArgs(ctypes.Structure):
@@ -50,6 +50,8 @@ EXPORTS = {
                                              P(c_i64)]),
     "craft_plan_layer_tables": (ctypes.c_int, [c_vp, c_i32, c_vp, c_vp, c_vp, c_vp]),
     "craft_plan_greedy_order": (ctypes.c_int, [c_vp, c_vp, c_i64, P(c_i64)]),
+    "craft_plan_benefit": (ctypes.c_int, [c_vp, P(c_i32), c_vp, c_vp, c_vp, P(ctypes.c_double),
+                                          P(c_i32)]),
     "craft_plan_rank_rows": (ctypes.c_int, [c_vp, c_i32, c_vp, c_vp, P(c_i32)]),
     "craft_plan_tables_bytes": (ctypes.c_int, [c_vp, c_i32, c_i32, P(c_sz)]),
     "craft_plan_tables_upload": (ctypes.c_int, [c_vp, c_i32, c_i32, c_vp, c_sz, c_vp]),
@@ -136,13 +138,14 @@ class Plan:
 
     def __init__(self, load: np.ndarray, D: int, budget_bytes: int,
                  bytes_per_replica: Optional[Sequence[int]] = None, gpus_per_node: int = 8,
-                 objective: int = 0):
+                 objective: int = 0, auto_r: bool = False):
         load = np.ascontiguousarray(load, dtype=np.int64)
         assert load.ndim == 3
         B, L, E = load.shape
         bpr = None if bytes_per_replica is None else np.ascontiguousarray(bytes_per_replica, np.int64)
         pp = PlanParams(L, E, D, gpus_per_node, B, load.ctypes.data,
-                        None if bpr is None else bpr.ctypes.data, int(budget_bytes), objective)
+                        None if bpr is None else bpr.ctypes.data, int(budget_bytes), objective,
+                        1 if auto_r else 0)
         h = c_vp()
         _check(lib().craft_plan(ctypes.byref(pp), ctypes.byref(h)), "craft_plan")
         self._h = h
@@ -182,6 +185,17 @@ class Plan:
         _check(lib().craft_plan_greedy_order(self._h, out.ctypes.data, n.value, n),
                "craft_plan_greedy_order")
         return out
+
+    def benefit(self) -> dict:
+        """Alg. 1's matrix as kept by an objective-1 plan."""
+        K, tot, aR = c_i32(), ctypes.c_double(), c_i32()
+        _check(lib().craft_plan_benefit(self._h, K, None, None, None, tot, aR), "craft_plan_benefit")
+        counts = np.empty(K.value, np.int32)
+        base = np.empty(self.L, np.float64)
+        gain = np.empty((K.value, self.L), np.float64)
+        _check(lib().craft_plan_benefit(self._h, K, counts.ctypes.data, base.ctypes.data,
+                                        gain.ctypes.data, tot, aR), "craft_plan_benefit")
+        return dict(counts=counts, base=base, gain=gain, total_gain=tot.value, auto_R=aR.value)
 
     def rank_rows(self, layer: int, counts: np.ndarray):
         counts = np.ascontiguousarray(counts, dtype=np.int64)

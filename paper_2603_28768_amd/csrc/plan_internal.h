@@ -26,6 +26,12 @@ struct craft_plan {
     int32_t L = 0, E = 0, D = 0, gpus_per_node = 0;
     std::vector<craft_layer_plan> layers;
     std::vector<int32_t> order;          // objective 0: layer that received each replica
+    // objective 1: Alg. 1's benefit matrix and what the allocation made of it
+    std::vector<int32_t> benefit_counts; // candidate replica counts 1, 2, 4, ..
+    std::vector<double> benefit_base;    // [L] placement-only mean balancedness
+    std::vector<double> benefit_gain;    // [K][L] mean balancedness gain at each count
+    double total_gain = 0.0;             // sum of the gains of the counts chosen
+    int32_t auto_R = 0;                  // replication factor picked in automatic mode
     std::mutex reg_mutex;
     std::vector<craft_table_reg> regs;   // device table buffers filled from this plan
 };

@@ -123,6 +123,153 @@ std::vector<std::vector<int32_t>> interleaved_capacity(const std::vector<int32_t
     return A;
 }
 
+// Objective 0.  One replica at a time to the layer whose estimated maximum rank load drops
+// most per byte; steps without gain are still taken while something fits the budget.
+void unit_greedy(const std::vector<int64_t> &ws, int32_t L, int32_t E, int32_t D,
+                 const std::vector<int64_t> &cost, int64_t budget, std::vector<int32_t> &x,
+                 std::vector<std::vector<int32_t>> &copies, std::vector<int32_t> &order) {
+    std::vector<int64_t> now(L), next(L, 0);
+    std::vector<std::vector<int32_t>> next_copies(L);
+    std::vector<char> have_next(L, 0);
+    for (int32_t l = 0; l < L; ++l) now[l] = max_rank_load(&ws[(size_t)l * E], copies[l], D);
+    int64_t spent = 0;
+    const int64_t cap_per_layer = (int64_t)E * (D - 1);
+    for (;;) {
+        int32_t pick = -1;
+        for (int32_t l = 0; l < L; ++l) {
+            if (cost[l] > budget - spent || x[l] >= cap_per_layer) continue;
+            if (!have_next[l]) {
+                next_copies[l] = copies[l];
+                int32_t e = hottest_per_copy(&ws[(size_t)l * E], next_copies[l], D);
+                if (e < 0) continue;
+                next_copies[l][e] += 1;
+                next[l] = max_rank_load(&ws[(size_t)l * E], next_copies[l], D);
+                have_next[l] = 1;
+            }
+            if (pick < 0) { pick = l; continue; }
+            // (now - next) / cost, larger first; then larger current maximum; then lower layer
+            wide_t lhs = (wide_t)(now[l] - next[l]) * cost[pick];
+            wide_t rhs = (wide_t)(now[pick] - next[pick]) * cost[l];
+            if (lhs > rhs || (lhs == rhs && now[l] > now[pick])) pick = l;
+        }
+        if (pick < 0) break;
+        x[pick] += 1;
+        spent += cost[pick];
+        copies[pick].swap(next_copies[pick]);
+        now[pick] = next[pick];
+        have_next[pick] = 0;
+        order.push_back(pick);
+    }
+}
+
+// Alg. 1.  For r = 0 and r = 1, 2, 4, .. <= D: place the layer once on the summed loads with
+// r replicas, then replay every batch under that placement (a copy of expert e carries
+// floor(W[b][l][e] / copies[e])) and average (mean rank load) / (maximum rank load) over the
+// batches.  base[l] = that mean at r = 0; gain[i][l] = mean at counts[i] minus base[l] (the
+// listing's scalar `base` is assigned from BAL[l], so it is read per layer).  A batch that
+// sends nothing to the layer scores 1.
+void replay_benefit(const int64_t *load, int64_t B, const std::vector<int64_t> &ws, int32_t L,
+                    int32_t E, int32_t D, craft_plan_t &plan) {
+    plan.benefit_counts.clear();
+    for (int64_t r = 1; r <= D && r <= (int64_t)E * (D - 1); r *= 2)
+        plan.benefit_counts.push_back((int32_t)r);
+    const size_t K = plan.benefit_counts.size();
+    plan.benefit_base.assign(L, 0.0);
+    plan.benefit_gain.assign(K * (size_t)L, 0.0);
+    std::vector<int64_t> G(D);
+    for (int32_t l = 0; l < L; ++l) {
+        const int64_t *wl = &ws[(size_t)l * E];
+        std::vector<int32_t> copies(E, 1);
+        int32_t have = 0;
+        for (size_t i = 0; i <= K; ++i) {
+            const int32_t r = i == 0 ? 0 : plan.benefit_counts[i - 1];
+            for (; have < r; ++have) copies[hottest_per_copy(wl, copies, D)] += 1;
+            Placement pl = place_copies(wl, copies, even_capacity(E + r, D));
+            double bal = 0.0;
+            for (int64_t b = 0; b < B; ++b) {
+                const int64_t *wb = load + ((size_t)b * L + l) * E;
+                int64_t mx = 0, sum = 0;
+                for (int32_t g = 0; g < D; ++g) {
+                    int64_t v = 0;
+                    for (auto &ec : pl.held[g]) v += wb[ec.first] / copies[ec.first];
+                    mx = std::max(mx, v);
+                    sum += v;
+                }
+                bal += mx == 0 ? 1.0 : ((double)sum / (double)D) / (double)mx;
+            }
+            const double mean = bal / (double)B;
+            if (i == 0) plan.benefit_base[l] = mean;
+            else plan.benefit_gain[(i - 1) * (size_t)L + l] = mean - plan.benefit_base[l];
+        }
+    }
+}
+
+// Alg. 2 for every capacity 0..C: value[c] = largest total gain of one count per layer from
+// {0} + counts that sums to exactly c; reach[c] = whether any selection does.  Counts are
+// tried in ascending order and only a strictly larger value replaces the incumbent, so ties
+// keep "no replica", then the smaller count.  choice[l][c] = count taken by layer l-1.
+struct Knapsack {
+    std::vector<double> value;
+    std::vector<char> reach;
+    std::vector<std::vector<int32_t>> choice;
+};
+Knapsack knapsack(const craft_plan_t &plan, int32_t L, int64_t C) {
+    const size_t K = plan.benefit_counts.size();
+    Knapsack k;
+    k.value.assign(C + 1, 0.0);
+    k.reach.assign(C + 1, 0);
+    k.reach[0] = 1;
+    k.choice.assign(L + 1, std::vector<int32_t>(C + 1, 0));
+    std::vector<double> nv(C + 1);
+    std::vector<char> nr(C + 1);
+    for (int32_t l = 1; l <= L; ++l) {
+        for (int64_t c = 0; c <= C; ++c) {
+            nv[c] = k.value[c];
+            nr[c] = k.reach[c];
+            for (size_t i = 0; i < K; ++i) {
+                const int64_t r = plan.benefit_counts[i];
+                if (c < r || !k.reach[c - r]) continue;
+                const double cand = k.value[c - r] + plan.benefit_gain[i * (size_t)L + (l - 1)];
+                if (!nr[c] || cand > nv[c]) { nv[c] = cand; nr[c] = 1; k.choice[l][c] = (int32_t)r; }
+            }
+        }
+        k.value.swap(nv);
+        k.reach.swap(nr);
+    }
+    return k;
+}
+
+// Sec. 4.2.1 steps 2 and 3.  The replica total is the budget (capped at what the candidate
+// counts can hold), or with auto_r the multiple R * D <= budget with the highest total gain
+// per replica (ties: smaller R); a total no selection reaches falls back to the next lower
+// one that is reachable.  Then Alg. 2's back-trace.
+void knapsack_allocation(craft_plan_t &plan, int32_t L, int32_t D, int64_t budget, bool auto_r,
+                         std::vector<int32_t> &x) {
+    x.assign(L, 0);
+    if (plan.benefit_counts.empty()) return;
+    int64_t cap = std::min<int64_t>(budget, (int64_t)L * plan.benefit_counts.back());
+    Knapsack k = knapsack(plan, L, cap);
+    if (auto_r) {
+        int64_t best_R = 0;
+        double best = 0.0;
+        for (int64_t R = 1; R * D <= cap; ++R) {
+            if (!k.reach[R * D]) continue;
+            const double per = k.value[R * D] / (double)(R * D);
+            if (best_R == 0 || per > best) { best_R = R; best = per; }
+        }
+        cap = best_R * D;
+        plan.auto_R = (int32_t)best_R;
+    }
+    while (!k.reach[cap]) cap -= 1;
+    plan.total_gain = k.value[cap];
+    int64_t c = cap;
+    for (int32_t l = L; l >= 1; --l) {
+        const int32_t r = k.choice[l][c];
+        x[l - 1] = r;
+        c -= r;
+    }
+}
+
 }  // namespace
 
 size_t craft_tables_words(int32_t E, int32_t S) {
@@ -183,7 +330,7 @@ craft_status craft_plan(const craft_plan_params *pp, craft_plan_t **out) {
     const int32_t L = pp->L, E = pp->E, D = pp->D;
     if (L <= 0 || E <= 0 || D <= 0 || pp->B <= 0 || !pp->load || pp->budget_bytes < 0)
         return CRAFT_EINVAL;
-    if (pp->objective != 0) return CRAFT_EINVAL;
+    if (pp->objective < 0 || pp->objective > 2) return CRAFT_EINVAL;
     if ((int64_t)E * D > (int64_t)1 << 30) return CRAFT_EINVAL;
     std::vector<int64_t> cost(L, 1);
     if (pp->bytes_per_replica)
@@ -191,54 +338,39 @@ craft_status craft_plan(const craft_plan_params *pp, craft_plan_t **out) {
             if (pp->bytes_per_replica[l] <= 0) return CRAFT_EINVAL;
             cost[l] = pp->bytes_per_replica[l];
         }
+    // objectives 1 and 2 count replicas, as the paper does: one size for every layer
+    if (pp->objective != 0)
+        for (int32_t l = 1; l < L; ++l)
+            if (cost[l] != cost[0]) return CRAFT_EINVAL;
+    for (size_t i = 0, n = (size_t)pp->B * L * E; i < n; ++i)
+        if (pp->load[i] < 0) return CRAFT_EINVAL;
     try {
         // Alg. 1: W_s = W summed over batches
         std::vector<int64_t> ws((size_t)L * E, 0);
         for (int64_t b = 0; b < pp->B; ++b)
             for (int32_t l = 0; l < L; ++l)
-                for (int32_t e = 0; e < E; ++e) {
-                    int64_t v = pp->load[((size_t)b * L + l) * E + e];
-                    if (v < 0) return CRAFT_EINVAL;
-                    ws[(size_t)l * E + e] += v;
-                }
+                for (int32_t e = 0; e < E; ++e)
+                    ws[(size_t)l * E + e] += pp->load[((size_t)b * L + l) * E + e];
 
         std::unique_ptr<struct craft_plan> plan(new struct craft_plan());
         plan->L = L; plan->E = E; plan->D = D; plan->gpus_per_node = pp->gpus_per_node;
 
-        // per-layer state of the unit greedy
         std::vector<std::vector<int32_t>> copies(L, std::vector<int32_t>(E, 1));
         std::vector<int32_t> x(L, 0);
-        std::vector<int64_t> now(L), next(L, 0);
-        std::vector<std::vector<int32_t>> next_copies(L);
-        std::vector<char> have_next(L, 0);
-        for (int32_t l = 0; l < L; ++l) now[l] = max_rank_load(&ws[(size_t)l * E], copies[l], D);
-        int64_t spent = 0;
-        const int64_t cap_per_layer = (int64_t)E * (D - 1);
-        for (;;) {
-            int32_t pick = -1;
-            for (int32_t l = 0; l < L; ++l) {
-                if (cost[l] > pp->budget_bytes - spent || x[l] >= cap_per_layer) continue;
-                if (!have_next[l]) {
-                    next_copies[l] = copies[l];
-                    int32_t e = hottest_per_copy(&ws[(size_t)l * E], next_copies[l], D);
-                    if (e < 0) continue;
-                    next_copies[l][e] += 1;
-                    next[l] = max_rank_load(&ws[(size_t)l * E], next_copies[l], D);
-                    have_next[l] = 1;
-                }
-                if (pick < 0) { pick = l; continue; }
-                // (now - next) / cost, larger first; then larger current maximum; then lower layer
-                wide_t lhs = (wide_t)(now[l] - next[l]) * cost[pick];
-                wide_t rhs = (wide_t)(now[pick] - next[pick]) * cost[l];
-                if (lhs > rhs || (lhs == rhs && now[l] > now[pick])) pick = l;
+        if (pp->objective == 0) {
+            unit_greedy(ws, L, E, D, cost, pp->budget_bytes, x, copies, plan->order);
+        } else {
+            const int64_t budget = pp->budget_bytes / cost[0];
+            if (pp->objective == 1) {
+                replay_benefit(pp->load, pp->B, ws, L, E, D, *plan);
+                knapsack_allocation(*plan, L, D, budget, pp->auto_r != 0, x);
+            } else {
+                const int64_t n = std::min<int64_t>(budget / L, (int64_t)E * (D - 1));
+                x.assign(L, (int32_t)n);
             }
-            if (pick < 0) break;
-            x[pick] += 1;
-            spent += cost[pick];
-            copies[pick].swap(next_copies[pick]);
-            now[pick] = next[pick];
-            have_next[pick] = 0;
-            plan->order.push_back(pick);
+            for (int32_t l = 0; l < L; ++l)
+                for (int32_t i = 0; i < x[l]; ++i)
+                    copies[l][hottest_per_copy(&ws[(size_t)l * E], copies[l], D)] += 1;
         }
 
         // Alg. 3 on the physical expert counts, then the final placement per layer
@@ -318,6 +450,19 @@ craft_status craft_plan_greedy_order(const craft_plan_t *plan, int32_t *layers, 
     if (!plan || !n || cap < 0 || (cap > 0 && !layers)) return CRAFT_EINVAL;
     *n = (int64_t)plan->order.size();
     for (int64_t i = 0; i < std::min(*n, cap); ++i) layers[i] = plan->order[(size_t)i];
+    return CRAFT_OK;
+}
+
+craft_status craft_plan_benefit(const craft_plan_t *plan, int32_t *n_counts, int32_t *counts,
+                                double *base, double *gain, double *total_gain, int32_t *auto_R) {
+    if (!plan) return CRAFT_EINVAL;
+    const size_t K = plan->benefit_counts.size();
+    if (n_counts) *n_counts = (int32_t)K;
+    if (counts) std::copy(plan->benefit_counts.begin(), plan->benefit_counts.end(), counts);
+    if (base) std::copy(plan->benefit_base.begin(), plan->benefit_base.end(), base);
+    if (gain) std::copy(plan->benefit_gain.begin(), plan->benefit_gain.end(), gain);
+    if (total_gain) *total_gain = plan->total_gain;
+    if (auto_R) *auto_R = plan->auto_R;
     return CRAFT_OK;
 }
 

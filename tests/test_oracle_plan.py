@@ -5,6 +5,7 @@ and closed forms, brute force on tiny inputs, hand-computed cases and invariants
 """
 import itertools
 import os
+from fractions import Fraction
 
 import numpy as np
 import pytest
@@ -322,3 +323,128 @@ def test_balancedness_is_one_for_equal_loads_and_is_avg_over_max():
 def test_realized_rows_and_heaviest_rank():
     assert po.realized_rank_rows([3, 1, 4, 1, 5], [0, 2, 3, 5]) == [4, 4, 6]
     assert po.heaviest_rank([4, 6, 6]) == 1
+
+
+# ------------------------------------------------- Alg. 1 replay, step 2, paper pipeline
+
+def _read_alg1_cases(path):
+    out = []
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, batches, base, scores = [f.strip() for f in line.split("|")]
+        W = [[[int(v) for v in b.split()]] for b in batches.split(";")]
+        out.append((name, W, float(Fraction(base)), [float(Fraction(v)) for v in scores.split()]))
+    return out
+
+
+def test_alg1_hand_worked_cases(golden_dir):
+    for name, W, base, scores in _read_alg1_cases(os.path.join(golden_dir, "alg1_hand_cases.txt")):
+        counts, b, T = po.replication_benefit(W, 4)
+        assert counts == [1, 2, 4], name
+        assert b == [base], name
+        assert [T[r][0] for r in counts] == [s - base for s in scores], name
+
+
+def test_alg1_base_is_per_layer():
+    # the gain of a layer must not depend on which other layers are planned with it
+    g = np.random.default_rng(77)
+    W = g.integers(0, 300, size=(3, 4, 10)).tolist()
+    counts, base, T = po.replication_benefit(W, 4)
+    for l in range(4):
+        Wl = [[W[b][l]] for b in range(3)]
+        c1, b1, T1 = po.replication_benefit(Wl, 4)
+        assert b1[0] == base[l]
+        assert all(T1[r][0] == T[r][l] for r in counts)
+
+
+def test_alg1_single_batch_base_is_the_placement_estimate():
+    # with one batch the replay of r = 0 scores exactly the planner's own estimate
+    g = np.random.default_rng(78)
+    W = g.integers(0, 1000, size=(1, 3, 12)).tolist()
+    _, base, _ = po.replication_benefit(W, 4)
+    ref = po.make_plan(W, 4, None, 0)
+    assert base == [lay["est_balancedness"] for lay in ref["layers"]]
+
+
+def test_alg1_scores_lie_in_unit_interval_and_counts_follow_D():
+    g = np.random.default_rng(79)
+    for D in (1, 2, 3, 4, 8, 16):
+        W = g.integers(0, 500, size=(2, 2, 16)).tolist()
+        counts, base, T = po.replication_benefit(W, D)
+        assert counts == [r for r in (1, 2, 4, 8, 16) if r <= D and D > 1]
+        for l in range(2):
+            assert 1.0 / D <= base[l] <= 1.0
+            for r in counts:
+                assert 1.0 / D - 1e-12 <= base[l] + T[r][l] <= 1.0 + 1e-12
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_step2_and_value_table_against_enumeration(seed):
+    g = np.random.default_rng(500 + seed)
+    L, D = int(g.integers(1, 4)), int(g.choice([2, 4]))
+    keys = [r for r in (1, 2, 4) if r <= D]
+    T = {r: [float(v) for v in g.integers(-2, 12, size=L)] for r in keys}
+    R_max = L                                     # at most D replicas per layer
+    # exhaustive: best value for every exact total
+    best = {}
+    for x in itertools.product([0] + keys, repeat=L):
+        val = sum(T[r][l] for l, r in enumerate(x) if r)
+        c = sum(x)
+        best[c] = val if c not in best or val > best[c] else best[c]
+    tab = po.mckp_table(T, R_max * D)
+    for c in range(R_max * D + 1):
+        assert tab[c] == best.get(c)
+    want, want_v = 0, None
+    for R in range(1, R_max + 1):
+        if R * D in best:
+            per = best[R * D] / (R * D)
+            if want == 0 or per > want_v:
+                want, want_v = R, per
+    assert po.choose_replication_factor(T, D, R_max) == want
+
+
+def test_paper_pipeline_totals_and_fallback():
+    g = np.random.default_rng(80)
+    W = g.integers(0, 400, size=(2, 3, 8)).tolist()
+    D = 4
+    reachable = {sum(x) for x in itertools.product((0, 1, 2, 4), repeat=3)}
+    for budget in range(0, 14):
+        p = po.make_plan_paper(W, D, budget)
+        assert p["total_replicas"] == max(c for c in reachable if c <= budget)
+        assert all(v in (0, 1, 2, 4) for v in p["x"])
+        assert p["total_gain"] == sum(p["benefit"][r][l] for l, r in enumerate(p["x"]) if r)
+        for l, lay in enumerate(p["layers"]):
+            assert sum(lay["copies"]) == 8 + p["x"][l] == len(lay["slot_expert"])
+    # one layer: totals 3 is not a candidate count -> falls back to 2
+    W1 = [[[50, 30, 5, 5]]]
+    assert po.make_plan_paper(W1, 4, 3)["x"] == [2]
+    # automatic mode spends a multiple of D
+    for budget in (4, 8, 12):
+        p = po.make_plan_paper(W, D, budget, auto_R=True)
+        assert p["total_replicas"] % D == 0 and 0 < p["total_replicas"] <= budget
+
+
+def test_paper_pipeline_puts_replicas_on_the_skewed_layer():
+    # Sec. 4.2.1's example: the skewed layer takes the replicas, the balanced one none
+    skew = [400, 10, 10, 10, 10, 10, 10, 10]
+    flat = [50, 50, 50, 50, 50, 50, 50, 50]
+    p = po.make_plan_paper([[skew, flat]], 4, 4)
+    assert p["x"] == [4, 0]
+
+
+def test_uniform_comparison_plans():
+    g = np.random.default_rng(81)
+    W = g.integers(0, 400, size=(2, 3, 8)).tolist()
+    base = po.make_plan_uniform(W, 4, 0)
+    assert base["x"] == [0, 0, 0] and base["total_replicas"] == 0
+    same = po.make_plan(W, 4, None, 0)
+    assert [l["slot_expert"] for l in base["layers"]] == [l["slot_expert"] for l in same["layers"]]
+    uni = po.make_plan_uniform(W, 4, 4)
+    assert uni["total_replicas"] == 3 * 4 and uni["memory_saving_vs_uniform"] == 1.0
+    for lay in uni["layers"]:
+        assert all(lay["rank_slot_off"][g + 1] - lay["rank_slot_off"][g] == 3 for g in range(4))
+        # replication can only lower the estimated maximum rank load
+    for l in range(3):
+        assert uni["layers"][l]["est_max_rank_load"] <= base["layers"][l]["est_max_rank_load"]

@@ -129,3 +129,90 @@ def test_budget_beyond_every_expert_on_every_rank_stops():
     p = binding.Plan(W, 2, 100)                 # at most E*(D-1) = 2 replicas exist
     assert p.summary()["total_replicas"] == 2
     assert p.layer(0)["copies"].tolist() == [2, 2]
+
+
+# ------------------------------------------- the paper's own pipeline and the comparison plans
+
+def _same_paper(plan: binding.Plan, ref: dict):
+    b = plan.benefit()
+    assert b["counts"].tolist() == ref["benefit_counts"]
+    assert b["base"].tolist() == ref["benefit_base"]                  # same double expressions
+    for i, r in enumerate(ref["benefit_counts"]):
+        assert b["gain"][i].tolist() == ref["benefit"][r]
+    assert b["total_gain"] == ref["total_gain"]
+    _same(plan, ref)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_paper_pipeline_matches_checker_on_random_loads(seed):
+    g = np.random.default_rng(900 + seed)
+    L, D = int(g.integers(1, 7)), int(g.choice([1, 2, 3, 4, 8, 16]))
+    E = int(g.integers(1, 30))
+    B = int(g.integers(1, 6))
+    W = (g.zipf(1.4, size=(B, L, E)) % int(g.choice([3, 200, 50000]))).astype(np.int64)
+    budget = int(g.integers(0, L * D + 4))
+    for auto in (False, True):
+        plan = binding.Plan(W, D, budget, objective=1, auto_r=auto)
+        ref = po.make_plan_paper(W.tolist(), D, budget, auto)
+        _same_paper(plan, ref)
+        if auto and ref["benefit_counts"]:
+            R = po.choose_replication_factor(ref["benefit"], D, min(budget, L * max(ref["benefit_counts"])) // D)
+            assert plan.benefit()["auto_R"] == R and plan.summary()["total_replicas"] <= R * D
+
+
+def test_paper_pipeline_counts_bytes_as_replicas():
+    g = np.random.default_rng(950)
+    W = g.integers(0, 900, size=(3, 4, 10))
+    plan = binding.Plan(W, 4, 7 * 1000 + 999, bytes_per_replica=[1000] * 4, objective=1)
+    _same_paper(plan, po.make_plan_paper(W.tolist(), 4, 7))
+    with pytest.raises(binding.CraftError):
+        binding.Plan(W, 4, 7000, bytes_per_replica=[1000, 1000, 1000, 999], objective=1)
+    with pytest.raises(binding.CraftError):
+        binding.Plan(W, 4, 7, objective=3)
+    assert binding.Plan(W, 4, 7).benefit()["counts"].size == 0       # objective 0 keeps no matrix
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_uniform_comparison_plans_match_checker(seed):
+    g = np.random.default_rng(970 + seed)
+    L, D, E = int(g.integers(1, 6)), int(g.choice([1, 2, 4, 8])), int(g.integers(1, 24))
+    W = g.integers(0, 3000, size=(2, L, E))
+    for n in (0, 1, D, 3 * D):
+        plan = binding.Plan(W, D, n * L + int(g.integers(0, L)), objective=2)
+        _same(plan, po.make_plan_uniform(W.tolist(), D, min(n, E * (D - 1))))
+
+
+def test_stack_shape_three_planners_side_by_side():
+    # 58 layers x 256 experts on 32 ranks, four profiling batches drawn around each layer's
+    # popularity.  At the same replica total: the paper's pipeline, the unit greedy and
+    # uniform spreading; and uniform replication at its own minimum L * D.
+    L, E, D, B = 58, 256, 32, 4
+    s = synth.trace_layer_exponents(L, 5)
+    g = np.random.default_rng(5)
+    W = np.stack([[g.multinomial(8 * 4096, synth.popularity(E, s[l], 5, l)) for l in range(L)]
+                  for _ in range(B)]).astype(np.int64)
+    total = 8 * D                                                       # R = 8
+    paper = binding.Plan(W, D, total, objective=1)
+    _same_paper(paper, po.make_plan_paper(W.tolist(), D, total))
+    greedy = binding.Plan(W, D, total)
+    spread = binding.Plan(W, D, total, objective=2)
+    uniform = binding.Plan(W, D, L * D, objective=2)
+    base = binding.Plan(W, D, 0, objective=2)
+
+    def mean_bal(p):
+        return float(np.mean([p.layer(l)["est_balancedness"] for l in range(L)]))
+
+    assert paper.summary()["total_replicas"] == total == greedy.summary()["total_replicas"]
+    assert uniform.summary()["memory_saving_vs_uniform"] == 1.0
+    assert paper.summary()["memory_saving_vs_uniform"] == L / 8            # Sec. 5.2: L / R
+    # benefit-driven allocation beats spreading the same replicas evenly (Sec. 3.2); uniform
+    # replication with L / R times the memory is the upper end of the curve
+    b0, bp, bg, bs, bu = (mean_bal(p) for p in (base, paper, greedy, spread, uniform))
+    assert bu > bp > bs > b0 and bg > bs
+    # skewed layers take the replicas
+    x = np.array([paper.layer(l)["n_replicas"] for l in range(L)])
+    assert x[s > 1.3].sum() > x[s < 0.9].sum()
+    # automatic mode lands on a multiple of D no larger than the budget
+    auto = binding.Plan(W, D, 16 * D, objective=1, auto_r=True)
+    R = auto.benefit()["auto_R"]
+    assert 1 <= R <= 16 and auto.summary()["total_replicas"] == R * D
