@@ -68,6 +68,12 @@ craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t
 craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, int32_t k,
                                int32_t E, int64_t batch_tokens, int64_t *counts, void *stream);
 
+/* Sec. 4.3 step 1, between two rebalancing windows: window[i] += counts[i] for the n int32
+ * per-expert counts a forward just produced (its `counts` output, or several layers' worth
+ * laid side by side).  The window is what craft_plan is fed at the next rebalancing.
+ *   counts DEVICE [n] int32;  window DEVICE [n] int64, updated in place. */
+craft_status craft_load_accumulate(const int32_t *counts, int64_t n, int64_t *window, void *stream);
+
 /* -------------------------------------------------------------------- planning
  * Host-side.  Decides how many replicas each layer gets under a memory budget, which
  * experts are copied, how many experts each rank holds per layer (Alg. 3) and which rank
@@ -151,6 +157,18 @@ craft_status craft_plan_benefit(const craft_plan_t *plan, int32_t *n_counts, int
  *   counts HOST [E];  rows HOST [D];  heaviest = rank with most rows (lowest id on ties). */
 craft_status craft_plan_rank_rows(const craft_plan_t *plan, int32_t layer, const int64_t *counts,
                                   int64_t *rows, int32_t *heaviest);
+
+/* Sec. 4.3 step 3: what one rank has to do to its weights of one layer when the plan changes.
+ * Slots of a rank are in ascending expert order in both plans.  A new slot whose expert the
+ * rank already holds reuses that slot's weights (the j-th copy of an expert on the rank
+ * matches the j-th old one); the others must be fetched from wherever the expert lives, and
+ * old slots left unmatched are dropped.  Both plans must agree on L, E and D.
+ *   reuse   HOST [slots of the rank in new_plan]: local index of the old slot whose weights
+ *           the new slot keeps, or -1 when they must be fetched;  may be NULL
+ *   n_fetch new slots to fetch;  n_drop old slots dropped;  either may be NULL */
+craft_status craft_plan_diff(const craft_plan_t *old_plan, const craft_plan_t *new_plan,
+                             int32_t layer, int32_t rank, int32_t *reuse, int32_t *n_fetch,
+                             int32_t *n_drop);
 
 /* Device copy of the tables one rank's forward needs.  Query the size, let the caller
  * allocate DEVICE memory (256-byte aligned), upload once, and pass the pointer to every

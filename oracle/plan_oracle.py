@@ -30,6 +30,8 @@ Steps and where they come from:
                         gain per replica.
   make_plan_paper       the paper's own pipeline: Alg. 1 -> (R) -> Alg. 2 -> Alg. 3 ->
                         placement.
+  plan_diff             Sec. 4.3 step 3: the weights a rank must fetch or may drop when
+                        one plan replaces another.
   make_plan_uniform     the comparison plans of Sec. 5: placement only (n = 0) and the
                         same number of replicas in every layer (n = D is the uniform
                         replication baseline).
@@ -407,6 +409,27 @@ def make_plan_uniform(W, D: int, n: int) -> dict:
     replication baseline (one replica per layer per rank); every layer gets n."""
     Ws = aggregate_load(W)
     return _finish_plan(Ws, D, [int(n)] * len(Ws), {})
+
+
+def plan_diff(old_layer: dict, new_layer: dict, g: int) -> Tuple[List[int], int, int]:
+    """Sec. 4.3 step 3 for one rank of one layer: which of its new slots keep weights the
+    rank already holds.  Plain multiset matching: every old slot can be reused once, by a new
+    slot of the same expert; equal experts pair up in slot order.  Returns (reuse[new local
+    slot] = old local slot or -1, slots to fetch, old slots dropped)."""
+    old = old_layer["slot_expert"][old_layer["rank_slot_off"][g]:old_layer["rank_slot_off"][g + 1]]
+    new = new_layer["slot_expert"][new_layer["rank_slot_off"][g]:new_layer["rank_slot_off"][g + 1]]
+    used = [False] * len(old)
+    reuse = []
+    for e in new:
+        hit = -1
+        for i, oe in enumerate(old):
+            if oe == e and not used[i]:
+                hit = i
+                break
+        if hit >= 0:
+            used[hit] = True
+        reuse.append(hit)
+    return reuse, sum(1 for r in reuse if r < 0), used.count(False)
 
 
 def realized_rank_rows(slot_cnt: Sequence[int], rank_slot_off: Sequence[int]) -> List[int]:

@@ -42,7 +42,9 @@ EXPORTS = {
     "craft_status_str": (ctypes.c_char_p, [ctypes.c_int]),
     "craft_route_topk": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp]),
     "craft_expert_load": (ctypes.c_int, [c_vp, c_i32, c_i64, c_i32, c_i32, c_i64, c_vp, c_vp]),
+    "craft_load_accumulate": (ctypes.c_int, [c_vp, c_i64, c_vp, c_vp]),
     "craft_plan": (ctypes.c_int, [P(PlanParams), P(c_vp)]),
+    "craft_plan_diff": (ctypes.c_int, [c_vp, c_vp, c_i32, c_i32, c_vp, P(c_i32), P(c_i32)]),
     "craft_plan_destroy": (None, [c_vp]),
     "craft_plan_summary": (ctypes.c_int, [c_vp, P(c_i32), P(c_i32), P(c_i32), P(c_i64),
                                           P(ctypes.c_double), P(ctypes.c_double)]),
@@ -131,6 +133,16 @@ def expert_load(topk_ids, E: int, batch_tokens: int, stream=None):
     return counts
 
 
+def load_accumulate(counts, window, stream=None):
+    """window (cuda int64) += counts (cuda int32), element by element."""
+    import torch
+    assert counts.dtype == torch.int32 and window.dtype == torch.int64
+    assert counts.numel() == window.numel() and counts.is_contiguous() and window.is_contiguous()
+    _check(lib().craft_load_accumulate(_dev(counts), counts.numel(), _dev(window),
+                                       _stream_ptr(stream)), "craft_load_accumulate")
+    return window
+
+
 # ----------------------------------------------------------------------- planning
 
 class Plan:
@@ -185,6 +197,15 @@ class Plan:
         _check(lib().craft_plan_greedy_order(self._h, out.ctypes.data, n.value, n),
                "craft_plan_greedy_order")
         return out
+
+    def diff(self, new: "Plan", layer: int, rank: int) -> dict:
+        """What `rank` does to its weights of `layer` when this plan is replaced by `new`."""
+        off = new.layer(layer)["rank_slot_off"]
+        reuse = np.empty(int(off[rank + 1] - off[rank]), np.int32)
+        nf, nd = c_i32(), c_i32()
+        _check(lib().craft_plan_diff(self._h, new._h, layer, rank, reuse.ctypes.data, nf, nd),
+               "craft_plan_diff")
+        return dict(reuse=reuse, n_fetch=nf.value, n_drop=nd.value)
 
     def benefit(self) -> dict:
         """Alg. 1's matrix as kept by an objective-1 plan."""

@@ -125,6 +125,14 @@ craft_status craft_expert_load(const int32_t *topk_ids, int32_t L, int64_t T, in
     return launch_expert_load(la, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
 
+craft_status craft_load_accumulate(const int32_t *counts, int64_t n, int64_t *window, void *stream) {
+    if (n < 0 || n > ((int64_t)1 << 40)) return CRAFT_EINVAL;
+    if (n == 0) return CRAFT_OK;
+    if (!counts || !window || !aligned(counts, 4) || !aligned(window, 8)) return CRAFT_EINVAL;
+    return launch_load_accumulate(counts, n, window, as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                        : CRAFT_EHIP;
+}
+
 craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,
                                       void *dev_tables, size_t bytes, void *stream) {
     if (!plan || !dev_tables || layer < 0 || layer >= plan->L || rank < 0 || rank >= plan->D)

@@ -112,5 +112,6 @@ struct LoadArgs {
     int64_t *counts;          // [B][L][E]
 };
 hipError_t launch_expert_load(const LoadArgs &a, hipStream_t s);
+hipError_t launch_load_accumulate(const int32_t *counts, int64_t n, int64_t *window, hipStream_t s);
 
 }  // namespace craft

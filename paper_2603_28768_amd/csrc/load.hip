@@ -83,6 +83,18 @@ __global__ __launch_bounds__(kThreads) void expert_load_kernel(LoadArgs a, int32
 
 }  // namespace
 
+// Sec. 4.3 step 1: the load window between two rebalancings grows by one forward's counts.
+__global__ void load_accumulate_kernel(const int32_t *counts, int64_t n, int64_t *window) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) window[i] += counts[i];
+}
+
+hipError_t launch_load_accumulate(const int32_t *counts, int64_t n, int64_t *window, hipStream_t s) {
+    hipLaunchKernelGGL(load_accumulate_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                       counts, n, window);
+    return hipGetLastError();
+}
+
 hipError_t launch_expert_load(const LoadArgs &a, hipStream_t s) {
     const int64_t cells = a.B * a.L;
     if (cells == 0) return hipSuccess;

@@ -489,6 +489,29 @@ craft_status craft_plan_rank_rows(const craft_plan_t *plan, int32_t layer, const
     return CRAFT_OK;
 }
 
+craft_status craft_plan_diff(const craft_plan_t *old_plan, const craft_plan_t *new_plan,
+                             int32_t layer, int32_t rank, int32_t *reuse, int32_t *n_fetch,
+                             int32_t *n_drop) {
+    if (!old_plan || !new_plan) return CRAFT_EINVAL;
+    if (old_plan->L != new_plan->L || old_plan->E != new_plan->E || old_plan->D != new_plan->D)
+        return CRAFT_EINVAL;
+    if (layer < 0 || layer >= new_plan->L || rank < 0 || rank >= new_plan->D) return CRAFT_EINVAL;
+    const craft_layer_plan &a = old_plan->layers[layer], &b = new_plan->layers[layer];
+    const int32_t a_lo = a.rank_slot_off[rank], a_hi = a.rank_slot_off[rank + 1];
+    const int32_t b_lo = b.rank_slot_off[rank], b_hi = b.rank_slot_off[rank + 1];
+    // both runs ascend by expert: one merge pass pairs equal experts in order
+    int32_t i = a_lo, fetch = 0, kept = 0;
+    for (int32_t j = b_lo; j < b_hi; ++j) {
+        while (i < a_hi && a.slot_expert[i] < b.slot_expert[j]) ++i;
+        const bool hit = i < a_hi && a.slot_expert[i] == b.slot_expert[j];
+        if (reuse) reuse[j - b_lo] = hit ? i - a_lo : -1;
+        if (hit) { ++i; ++kept; } else ++fetch;
+    }
+    if (n_fetch) *n_fetch = fetch;
+    if (n_drop) *n_drop = (a_hi - a_lo) - kept;
+    return CRAFT_OK;
+}
+
 craft_status craft_plan_tables_bytes(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                      size_t *bytes) {
     if (!plan || !bytes || layer < 0 || layer >= plan->L || rank < 0 || rank >= plan->D)
