@@ -247,11 +247,11 @@ def main():
             "--gpus above 1 is not part of this build")
         sys.exit(2)
 
+    import torch                        # before the library: both must share one HIP runtime
     from paper_2603_28768_amd import binding, synth
     binding.lib()                       # fail loudly if the HIP library is missing
     if args.config == "plan_curves":
         return plan_curves(args)
-    import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.config == "trace_load":
         return bench_trace_load(args)

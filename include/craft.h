@@ -265,6 +265,14 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
 craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                     const craft_fwd_args *args, void *stream);
 
+/* The most rows a row-tile of the two grouped GEMMs gets in forwards with these arguments
+ * (a multiple of 32).  With packed weights it is chosen per (plan, layer, rank, T, k, H, I)
+ * from the loads the plan was made from, so that the tiles of the busy slots fill the CUs
+ * in whole rounds; the choice is kept in the plan.  Host-side, no device work. */
+craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                          const craft_fwd_args *args, int32_t *rows_gateup,
+                                          int32_t *rows_down);
+
 /* After the caller has synchronised the stream: what the last forward on this workspace
  * found.  rows = rows routed to the rank; overflow != 0 when rows > max_rows (nothing was
  * computed).  Copies 16 bytes from the device, synchronously. */

@@ -61,6 +61,7 @@ EXPORTS = {
     "craft_pack_weights": (ctypes.c_int, [c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp]),
     "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
     "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
+    "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32)]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
     "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
     "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
@@ -80,6 +81,9 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise CraftError(f"{LIB_PATH} is missing: build it first "
                              "(python -m paper_2603_28768_amd.build)")
+        # torch first: the library has to bind to the HIP runtime torch brings along, or
+        # streams and device pointers made by one runtime meet kernels registered in another
+        import torch  # noqa: F401
         l = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in EXPORTS.items():
             f = getattr(l, name)
@@ -338,6 +342,14 @@ class RankForward:
                                             ctypes.byref(self.args), _stream_ptr(stream)),
                "craft_moe_rank_forward")
         return self.out
+
+    def tile_rows(self):
+        """(gate/up, down) row-tile heights the forward uses."""
+        g, d = c_i32(), c_i32()
+        _check(lib().craft_moe_rank_forward_tiles(self.plan._h, self.layer, self.rank,
+                                                  ctypes.byref(self.args), g, d),
+               "craft_moe_rank_forward_tiles")
+        return g.value, d.value
 
     def result(self):
         """(rows routed to the rank, overflow flag) of the last forward; synchronises."""

@@ -64,28 +64,45 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     const unsigned long long live = __ballot(mine);
     const T *y = static_cast<const T *>(a.y);
     T *out = static_cast<T *>(a.out) + t * a.H;
-    // the chunk loop is uniform over the wave (shuffles need every lane); a lane past the end
-    // of the row only skips its loads and its store
-    for (int base = 0; base < a.H; base += 64 * N) {
-        const int c0 = base + lane * N;
-        const bool inside = c0 < a.H;
-        float acc[N];
+    // The chunk loop is uniform over the wave (shuffles need every lane); a lane past the end
+    // of the row only skips its loads and its store.  Four chunks per lane are requested
+    // together, so a wave has four independent loads in flight per assignment instead of a
+    // chain of dependent ones.
+    constexpr int U = 4;
+    for (int base = 0; base < a.H; base += 64 * N * U) {
+        int c0[U];
+        bool inside[U];
+        float acc[U][N];
 #pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] = 0.0f;
+        for (int u = 0; u < U; ++u) {
+            c0[u] = base + (u * 64 + lane) * N;
+            inside[u] = c0[u] < a.H;
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[u][i] = 0.0f;
+        }
         unsigned long long m = live;
         while (m) {
             const int j = __ffsll((long long)m) - 1;
             m &= m - 1;
             const int32_t dj = __shfl(d, j, 64);
             const float wv = __shfl(wj, j, 64);
-            if (inside) {
-                float v[N];
-                Chunk<T>::load(y + (int64_t)(dj - lo) * a.H + c0, v);
+            const T *row = y + (int64_t)(dj - lo) * a.H;
+            float v[U][N];
 #pragma unroll
-                for (int i = 0; i < N; ++i) acc[i] += wv * v[i];
+            for (int u = 0; u < U; ++u) {
+                if (inside[u]) Chunk<T>::load(row + c0[u], v[u]);
+                else
+#pragma unroll
+                    for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[u][i] += wv * v[u][i];
         }
-        if (inside) Chunk<T>::store(out + c0, acc);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (inside[u]) Chunk<T>::store(out + c0[u], acc[u]);
     }
 }
 

@@ -167,21 +167,28 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         sorted_rows[pos] = mine;
     }
     __syncthreads();
-    int32_t mcarry = 0;
-    for (int32_t base = 0; base < nslots; base += kScanThreads) {
-        const int32_t pos = base + threadIdx.x;
-        int32_t mt = 0;
-        if (pos < nslots && !ovf) mt = (sorted_rows[pos] + a.bm - 1) / a.bm;
-        int32_t chunk_total;
-        const int32_t off = mcarry + block_exclusive_scan(mt, wsum, &chunk_total);
-        if (pos < nslots) a.mt_start[pos] = off;
-        mcarry += chunk_total;
+    // row-tiles per slot: its 32-row fragments over the launch's tile height, rounded up
+    int32_t mtotal[2];
+    for (int kind = 0; kind < 2; ++kind) {
+        const int32_t fmax = abs(kind == 0 ? a.frags_gu : a.frags_dn);
+        int32_t *mt_out = a.mt_start + kind * (nslots + 1);
+        int32_t mcarry = 0;
+        for (int32_t base = 0; base < nslots; base += kScanThreads) {
+            const int32_t pos = base + threadIdx.x;
+            int32_t mt = 0;
+            if (pos < nslots && !ovf) mt = (((sorted_rows[pos] + 31) >> 5) + fmax - 1) / fmax;
+            int32_t chunk_total;
+            const int32_t off = mcarry + block_exclusive_scan(mt, wsum, &chunk_total);
+            if (pos < nslots) mt_out[pos] = off;
+            mcarry += chunk_total;
+        }
+        if (threadIdx.x == 0) mt_out[nslots] = mcarry;
+        mtotal[kind] = mcarry;
     }
     if (threadIdx.x == 0) {
-        a.mt_start[nslots] = mcarry;
         a.ctrl[CTRL_ROWS] = rank_rows;
         a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
-        a.ctrl[CTRL_MTILES] = mcarry;
+        a.ctrl[CTRL_MTILES] = mtotal[0];
         a.ctrl[CTRL_TICKET] = 0;
     }
 }

@@ -30,7 +30,7 @@ namespace craft {
 namespace {
 
 // ------------------------------------------------------------------ bf16 / MFMA
-constexpr int BM = kBM_bf16;      // activation rows per tile
+constexpr int BM = kFragsBf16 * 32; // most activation rows per tile
 constexpr int BK = 64;            // contraction slab
 constexpr int ROWB = BK * 2 + 16; // padded LDS row, bytes
 constexpr int TILEB = 128 * ROWB; // one operand tile
@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256, 2) void ffn_bf16_kernel(FfnArgs a) {
     constexpr int BN = GATEUP ? 64 : 128;          // output columns per tile
     const int nt = (N + BN - 1) / BN;
     const int nk = (K + BK - 1) / BK;
-    const int64_t total = (int64_t)a.mt_start[a.nslots] * nt;
+    const int32_t *mt_start = a.mt_start + (GATEUP ? 0 : a.nslots + 1);
+    const int64_t total = (int64_t)mt_start[a.nslots] * nt;
     const int32_t lo_pos = a.slot_off[a.s_lo];
     const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
 
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256, 2) void ffn_bf16_kernel(FfnArgs a) {
     const int frag_off = (lane & 31) * ROWB + (lane >> 5) * 16;
 
     for (int64_t w = xcd_major_id(); w < total; w += gridDim.x) {
-        const Tile t = decode_tile(a, w, nt, BM, BN);
+        const Tile t = decode_tile(a, mt_start, w, nt, BN, GATEUP ? a.frags_gu : a.frags_dn);
         const unsigned short *wa = static_cast<const unsigned short *>(
             GATEUP ? a.w_gate[t.slot] : a.w_down[t.slot]);
         const unsigned short *wb = GATEUP ? static_cast<const unsigned short *>(a.w_up[t.slot]) : wa;
@@ -170,7 +171,7 @@ __global__ __launch_bounds__(256, 2) void ffn_bf16_kernel(FfnArgs a) {
 }
 
 // ------------------------------------------------------------------------ fp32
-constexpr int FM = kBM_f32;       // rows per tile
+constexpr int FM = kFragsF32 * 32;  // rows per tile
 constexpr int FN = 32;            // output columns per tile
 constexpr int FK = 32;            // contraction slab
 
@@ -183,12 +184,13 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(FfnArgs a) {
     const int K = GATEUP ? a.H : a.I;
     const int N = GATEUP ? a.I : a.H;
     const int nt = (N + FN - 1) / FN;
-    const int64_t total = (int64_t)a.mt_start[a.nslots] * nt;
+    const int32_t *mt_start = a.mt_start + (GATEUP ? 0 : a.nslots + 1);
+    const int64_t total = (int64_t)mt_start[a.nslots] * nt;
     const int32_t lo_pos = a.slot_off[a.s_lo];
     const float *xin = static_cast<const float *>(GATEUP ? a.x : a.act);
 
     for (int64_t w = xcd_major_id(); w < total; w += gridDim.x) {
-        const Tile t = decode_tile(a, w, nt, FM, FN);
+        const Tile t = decode_tile(a, mt_start, w, nt, FN, GATEUP ? a.frags_gu : a.frags_dn);
         const float *wa = static_cast<const float *>(GATEUP ? a.w_gate[t.slot] : a.w_down[t.slot]);
         const float *wb = GATEUP ? static_cast<const float *>(a.w_up[t.slot]) : wa;
         const float *xrow[4], *warow[4], *wbrow[4];

@@ -18,63 +18,62 @@ struct Tile {
     int32_t pos0;      // global dispatch position of the slot's first row
 };
 
-// Flattened work item w -> tile.  nt = column tiles per slot, bm/bn tile extents.
-static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, int64_t w, int32_t nt, int32_t bm,
-                                            int32_t bn) {
-    const int32_t qn = (int32_t)(w / nt);
-    int32_t lo = 0, hi = a.nslots;                 // find s: mt_start[s] <= qn < mt_start[s+1]
-    while (hi - lo > 1) {
-        const int32_t mid = (lo + hi) >> 1;
-        if (a.mt_start[mid] <= qn) lo = mid; else hi = mid;
-    }
-    const int32_t mt_first = a.mt_start[lo];
-    const int32_t mts = a.mt_start[lo + 1] - mt_first;
-    const int32_t s = a.order[lo];             // the list is ordered busiest slot first
-    const int32_t rem = (int32_t)(w - (int64_t)mt_first * nt);
-    Tile t;
-    t.slot = s;
-    t.m0 = (rem % mts) * bm;
-    t.n0 = (rem / mts) * bn;
-    t.pos0 = a.slot_off[a.s_lo + s];
-    t.rows = min(bm, a.slot_off[a.s_lo + s + 1] - t.pos0 - t.m0);
-    return t;
-}
-
-// The same walk over a copy of the three small tables held in LDS (loaded once per
-// workgroup), which takes the chain of dependent global reads out of every tile's start.
+// Flattened work item w -> tile.  nt = column tiles per slot, bn = columns per tile.
+// mt_start[p] = row-tiles before position p of the busiest-first slot order.  A slot's rows
+// are cut into F 32-row fragments and m = ceil(F / f) row-tiles, either f fragments each with
+// a remainder at the end, or shared as evenly as whole fragments allow (row-tile i takes
+// fragments floor(i F / m) .. floor((i+1) F / m)); the launch says which.
 struct TileTables {
     static constexpr int kMaxSlots = 256;
     int32_t mt_start[kMaxSlots + 1];
     int32_t order[kMaxSlots];
     int32_t slot_off[kMaxSlots + 1];      // offsets of the rank's slots, busiest-first order undone
 };
-static __device__ __forceinline__ void load_tile_tables(const FfnArgs &a, TileTables &tt) {
+static __device__ __forceinline__ void load_tile_tables(const FfnArgs &a, const int32_t *mt_start,
+                                                        TileTables &tt) {
     for (int i = threadIdx.x; i <= a.nslots; i += blockDim.x) {
-        tt.mt_start[i] = a.mt_start[i];
+        tt.mt_start[i] = mt_start[i];
         tt.slot_off[i] = a.slot_off[a.s_lo + i];
         if (i < a.nslots) tt.order[i] = a.order[i];
     }
     __syncthreads();
 }
-static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, const TileTables &tt, int64_t w,
-                                                   int32_t nt, int32_t bm, int32_t bn) {
+// MT, ORD, OFF: the three tables, in global memory or in a workgroup's LDS copy
+// fmax > 0: row-tiles of fmax fragments and a remainder; fmax < 0: |fmax| at most, shared evenly
+template <typename MT, typename ORD, typename OFF>
+static __device__ __forceinline__ Tile decode_tile_in(int32_t nslots, const MT &mt_start, const ORD &order,
+                                                      const OFF &slot_off, int64_t w, int32_t nt, int32_t bn,
+                                                      int32_t fmax) {
     const int32_t qn = (int32_t)(w / nt);
-    int32_t lo = 0, hi = a.nslots;
+    int32_t lo = 0, hi = nslots;                   // find p: mt_start[p] <= qn < mt_start[p+1]
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
-        if (tt.mt_start[mid] <= qn) lo = mid; else hi = mid;
+        if (mt_start[mid] <= qn) lo = mid; else hi = mid;
     }
-    const int32_t mt_first = tt.mt_start[lo];
-    const int32_t mts = tt.mt_start[lo + 1] - mt_first;
-    const int32_t s = tt.order[lo];
+    const int32_t mt_first = mt_start[lo];
+    const int32_t mts = mt_start[lo + 1] - mt_first;
+    const int32_t s = order[lo];
     const int32_t rem = (int32_t)(w - (int64_t)mt_first * nt);
+    const int32_t i = rem % mts;
     Tile t;
     t.slot = s;
-    t.m0 = (rem % mts) * bm;
+    t.pos0 = slot_off[s];
+    const int32_t slot_rows = slot_off[s + 1] - t.pos0;
+    const int32_t frags = (slot_rows + 31) >> 5;
+    const int32_t f0 = fmax > 0 ? i * fmax : (int32_t)((int64_t)i * frags / mts);
+    const int32_t f1 = fmax > 0 ? min(f0 + fmax, frags) : (int32_t)((int64_t)(i + 1) * frags / mts);
+    t.m0 = f0 * 32;
+    t.rows = min(f1 * 32, slot_rows) - t.m0;
     t.n0 = (rem / mts) * bn;
-    t.pos0 = tt.slot_off[s];
-    t.rows = min(bm, tt.slot_off[s + 1] - t.pos0 - t.m0);
     return t;
+}
+static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, const int32_t *mt_start, int64_t w,
+                                                   int32_t nt, int32_t bn, int32_t fmax) {
+    return decode_tile_in(a.nslots, mt_start, a.order, a.slot_off + a.s_lo, w, nt, bn, fmax);
+}
+static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, const TileTables &tt, int64_t w,
+                                                   int32_t nt, int32_t bn, int32_t fmax) {
+    return decode_tile_in(a.nslots, tt.mt_start, tt.order, tt.slot_off, w, nt, bn, fmax);
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin; give each XCD a contiguous run of the

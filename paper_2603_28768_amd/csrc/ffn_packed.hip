@@ -224,8 +224,9 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
     __shared__ int64_t next_item;
     __shared__ TileTables tt;
+    const int32_t *mt_start = a.mt_start + (GATEUP ? 0 : a.nslots + 1);
     const bool small = a.nslots <= TileTables::kMaxSlots;
-    if (small) load_tile_tables(a, tt);
+    if (small) load_tile_tables(a, mt_start, tt);
     const int K = GATEUP ? a.H : a.I;
     const int N = GATEUP ? a.I : a.H;
     constexpr int GC = GATEUP ? 16 : 32;           // output columns per weight group
@@ -233,20 +234,22 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     const int ngroups = (N + GC - 1) / GC;
     const int nt = (N + BN - 1) / BN;
     const int nk4 = (K + 255) / 256;               // groups of four 64-wide slabs
-    const int64_t total = (int64_t)a.mt_start[a.nslots] * nt;
+    const int64_t total = (int64_t)mt_start[a.nslots] * nt;
     const int32_t lo_pos = a.slot_off[a.s_lo];
+    const int32_t fmax = GATEUP ? a.frags_gu : a.frags_dn;
     int32_t *counter = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
 
     int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
-        const Tile t = small ? decode_tile(a, tt, w, nt, kBM_packed, BN) : decode_tile(a, w, nt, kBM_packed, BN);
+        const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
         switch ((t.rows + 31) >> 5) {              // live 32-row fragments of this tile
             case 1: packed_tile<GATEUP, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             case 2: packed_tile<GATEUP, 2>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 3:
+            case 3: packed_tile<GATEUP, 3>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             case 4: packed_tile<GATEUP, 4>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 5:
+            case 5: packed_tile<GATEUP, 5>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             case 6: packed_tile<GATEUP, 6>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            case 7: packed_tile<GATEUP, 7>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             default: packed_tile<GATEUP, 8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
         }
         if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
@@ -288,7 +291,7 @@ hipError_t launch_packed(const FfnArgs &a, hipStream_t s) {
     const int N = GATEUP ? a.I : a.H;
     const int bn = GATEUP ? 128 : 256;
     const int64_t nt = (N + bn - 1) / bn;
-    const int64_t bound = (a.max_rows / kBM_packed + a.nslots) * nt;
+    const int64_t bound = (a.max_rows / (32 * std::abs(GATEUP ? a.frags_gu : a.frags_dn)) + a.nslots) * nt;
     int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu);
     grid = std::max<int64_t>(8, (grid + 7) / 8 * 8);
     hipLaunchKernelGGL(ffn_packed_kernel<GATEUP>, dim3((unsigned)grid), dim3(256), 0, s, a);

@@ -1,8 +1,11 @@
 // Device-side entry points of the C ABI: argument checks, workspace layout, launches.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <mutex>
+#include <queue>
 #include <vector>
 
 #include "kernels.h"
@@ -41,7 +44,7 @@ Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, i
     L.counts = take((size_t)E * 4);
     L.slot_cnt = take((size_t)S * 4);
     L.slot_off = take((size_t)(S + 1) * 4);
-    L.mt_start = take((size_t)(nslots + 1) * 4);
+    L.mt_start = take((size_t)(nslots + 1) * 4 * 2);
     L.order = take((size_t)(nslots + 1) * 4);
     L.act = take((size_t)L.max_rows * I * es);
     L.y = take((size_t)L.max_rows * H * es);
@@ -87,6 +90,87 @@ int cached_num_cu() {
         if (n <= 0) n = 256;
     }
     return n;
+}
+
+// ---- row-tile height of the packed FFN ---------------------------------------------------
+// A row-tile may have 4 to 8 fragments of 32 rows.  Taller tiles reuse a weight fragment more
+// often, but the tiles of the busy slots must also come out as whole rounds over the CUs: 176
+// tiles of 8 fragments on 256 CUs take as long as 256 would.  The height is chosen per GEMM by
+// playing the launch through on the host: expected rows per slot from the profiled loads the
+// plan was made from (scaled to this batch), tiles handed to the first free CU in list order,
+// with a tile costing a fixed part (starting it and streaming its weight block through one
+// CU) plus a part per fragment.  The constants are fitted to tile timings on MI355X under
+// full load; replayed against measured sweeps of the height on three workloads the model
+// picks the fastest or second-fastest height each time.
+double ffn_makespan(const std::vector<double> &slot_rows, int32_t frags, bool even, int64_t nt,
+                    double fixed_us, double frag_us, int32_t cus) {
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int32_t i = 0; i < cus; ++i) free_at.push(0.0);
+    double end = 0.0;
+    for (double r : slot_rows) {
+        const int64_t F = (int64_t)((r + 31.0) / 32.0);
+        if (F <= 0) continue;
+        const int64_t m = (F + frags - 1) / frags;
+        for (int64_t n = 0; n < nt; ++n)
+            for (int64_t i = 0; i < m; ++i) {
+                const int64_t f = even ? (i + 1) * F / m - i * F / m : std::min<int64_t>(frags, F - i * frags);
+                const double t = free_at.top() + fixed_us + frag_us * (double)f;
+                free_at.pop();
+                free_at.push(t);
+                end = std::max(end, t);
+            }
+    }
+    return end;
+}
+
+std::pair<int32_t, int32_t> choose_tile_frags(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                              int64_t T, int32_t k, int32_t H, int32_t I, int32_t cus) {
+    const craft_layer_plan &lp = plan->layers[layer];
+    std::pair<int32_t, int32_t> best{kFragsPacked, kFragsPacked};
+    double total = 0.0;
+    for (int64_t v : lp.expert_load) total += (double)v;
+    if (total <= 0.0 || T <= 0) return best;
+    std::vector<double> rows;
+    for (int32_t p = lp.rank_slot_off[rank]; p < lp.rank_slot_off[rank + 1]; ++p) {
+        const int32_t e = lp.slot_expert[p];
+        // a slot expected to see a fraction of a row is counted with one: it costs a tile per
+        // column block as soon as a single token reaches it
+        const double est = (double)(lp.expert_load[e] / lp.copies[e]) * (double)T * k / total;
+        rows.push_back(est >= 0.2 ? std::max(1.0, est) : 0.0);
+    }
+    std::sort(rows.begin(), rows.end(), std::greater<double>());
+    for (int kind = 0; kind < 2; ++kind) {
+        const int64_t K = kind == 0 ? H : I, N = kind == 0 ? I : H;
+        const int64_t nt = kind == 0 ? (N + 127) / 128 : (N + 255) / 256;
+        // microseconds per tile under full load, linear in the contraction length K; from
+        // per-tile device timestamps at K = 4096 and 7168 (gate/up) and 1536 and 2048 (down)
+        const double fixed_us = kind == 0 ? 20.0 + 0.0055 * (double)K : 21.0 + 0.0020 * (double)K;
+        const double frag_us = kind == 0 ? 1.5 + 0.00182 * (double)K : 0.1 + 0.00234 * (double)K;
+        double best_t = 0.0;
+        for (int32_t f = kFragsPacked; f >= 4; --f)
+            for (int even = 0; even < 2; ++even) {
+                const double t = ffn_makespan(rows, f, even != 0, nt, fixed_us, frag_us, cus);
+                if ((f == kFragsPacked && !even) || t < best_t * 0.98) {    // a change has to earn it
+                    best_t = t;
+                    (kind == 0 ? best.first : best.second) = even ? -f : f;
+                }
+            }
+    }
+    return best;
+}
+
+std::pair<int32_t, int32_t> tile_frags_for(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                           const craft_fwd_args *a, bool packed) {
+    if (a->dtype != CRAFT_BF16) return {kFragsF32, kFragsF32};
+    if (!packed) return {kFragsBf16, kFragsBf16};
+    craft_plan_t *p = const_cast<craft_plan_t *>(plan);
+    const std::array<int64_t, 6> key{layer, rank, a->T, a->k, a->H, a->I};
+    std::lock_guard<std::mutex> lk(p->reg_mutex);
+    auto it = p->tile_cache.find(key);
+    if (it == p->tile_cache.end())
+        it = p->tile_cache.emplace(key, choose_tile_frags(plan, layer, rank, a->T, a->k, a->H, a->I,
+                                                           cached_num_cu())).first;
+    return it->second;
 }
 
 craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a) {
@@ -230,6 +314,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     int32_t *mt_start = reinterpret_cast<int32_t *>(ws + L.mt_start);
     int32_t *order = reinterpret_cast<int32_t *>(ws + L.order);
     const bool packed = a->w_gateup_packed && a->w_down_packed;
+    const std::pair<int32_t, int32_t> frags = tile_frags_for(plan, layer, rank, a, packed);
     const int32_t *tables = static_cast<const int32_t *>(a->tables);
 
     // 1 route (+ per-block ranks and counts); user copies of ids / weights are written by the
@@ -244,8 +329,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 2 per-expert totals, slot offsets, tile table
     {
         ScopedEvent ev(CRAFT_K_SCAN, s);
-        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi,
-                    a->dtype == CRAFT_BF16 ? (packed ? kBM_packed : kBM_bf16) : kBM_f32, L.max_rows,
+        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi, frags.first, frags.second, L.max_rows,
                     counts, slot_cnt, slot_off, mt_start, order, ctrl,
                     a->counts, a->slot_cnt, a->slot_off};
         if (launch_scan(sa, s) != hipSuccess) return CRAFT_EHIP;
@@ -259,7 +343,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 4 grouped FFN
     FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, order, ctrl,
                a->w_gate, a->w_up, a->w_down, a->w_gateup_packed, a->w_down_packed,
-               ws + L.act, ws + L.y, L.max_rows, cached_num_cu()};
+               ws + L.act, ws + L.y, L.max_rows, cached_num_cu(), frags.first, frags.second};
     if (a->T > 0) {
         {
             ScopedEvent ev(CRAFT_K_GATEUP, s);
@@ -278,6 +362,18 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
         CombineArgs ca{a->dtype, a->T, a->k, a->H, ws + L.y, dest, w_out, slot_off, s_lo, s_hi, ctrl, a->out};
         if (launch_combine(ca, s) != hipSuccess) return CRAFT_EHIP;
     }
+    return CRAFT_OK;
+}
+
+craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                          const craft_fwd_args *a, int32_t *rows_gateup,
+                                          int32_t *rows_down) {
+    craft_status st = check_fwd(plan, layer, rank, a);
+    if (st != CRAFT_OK) return st;
+    const bool packed = a->w_gateup_packed && a->w_down_packed;
+    const std::pair<int32_t, int32_t> f = tile_frags_for(plan, layer, rank, a, packed);
+    if (rows_gateup) *rows_gateup = 32 * std::abs(f.first);
+    if (rows_down) *rows_down = 32 * std::abs(f.second);
     return CRAFT_OK;
 }
 

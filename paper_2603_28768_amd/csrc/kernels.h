@@ -19,10 +19,12 @@ enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
        CTRL_WORK_GATEUP = 4, CTRL_WORK_DOWN = 5,   // dynamic tile counters of the two GEMMs
        CTRL_WORDS = 16 };
 
-// Rows per row-tile of the grouped GEMMs (the unit the tile table counts in).
-constexpr int kBM_bf16 = 128;      // LDS-staged bf16 kernels (row-major weights)
-constexpr int kBM_packed = 256;    // weight-streaming bf16 kernels (packed weights)
-constexpr int kBM_f32 = 32;
+// Most 32-row fragments a row-tile of the grouped GEMMs may have (the tile table is built for
+// a height chosen per launch, up to these).
+constexpr int kFragsBf16 = 4;      // LDS-staged bf16 kernels (row-major weights): 128 rows
+constexpr int kFragsPacked = 8;    // weight-streaming bf16 kernels (packed weights): 256 rows
+constexpr int kFragsF32 = 1;
+constexpr int kBM_packed = kFragsPacked * 32;
 
 struct RouteArgs {
     const float *logits;
@@ -41,12 +43,13 @@ struct ScanArgs {
     int32_t NB, E;
     const int32_t *tables;    // device tables of this (layer, rank)
     int32_t S, s_lo, s_hi;
-    int32_t bm;               // rows per row-tile
+    int32_t frags_gu, frags_dn;   // most 32-row fragments per row-tile, gate/up and down GEMM (sign: see FfnArgs)
     int64_t max_rows;
     int32_t *counts;          // [E]
     int32_t *slot_cnt;        // [S]
     int32_t *slot_off;        // [S+1]
-    int32_t *mt_start;        // [s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot first
+    int32_t *mt_start;        // [2][s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot
+                              // first: for the gate/up GEMM, then for the down GEMM
     int32_t *order;           // [s_hi - s_lo] local slot at each position of that order
     int32_t *ctrl;
     int32_t *user_counts, *user_slot_cnt, *user_slot_off;   // optional copies
@@ -73,7 +76,7 @@ struct FfnArgs {
     const void *x;                 // [T][H]
     const int32_t *src;            // [A]
     const int32_t *slot_off;       // [S+1]
-    const int32_t *mt_start;       // [nslots+1]
+    const int32_t *mt_start;       // [2][nslots+1]: gate/up, down
     const int32_t *order;          // [nslots]
     int32_t *ctrl;
     const void *const *w_gate, *const *w_up, *const *w_down;   // row-major weights per slot
@@ -82,6 +85,8 @@ struct FfnArgs {
     void *y;                       // [max_rows][H]
     int64_t max_rows;
     int32_t num_cu;
+    int32_t frags_gu, frags_dn;    // most 32-row fragments per row-tile the tile tables were built for;
+                                   // negative: fragments shared evenly among a slot's row-tiles
 };
 hipError_t launch_gateup(const FfnArgs &a, hipStream_t s);
 hipError_t launch_down(const FfnArgs &a, hipStream_t s);

@@ -1,8 +1,11 @@
 // Internal layout of the plan object and of the per-rank device tables.
 #pragma once
 
+#include <array>
 #include <cstdint>
+#include <map>
 #include <mutex>
+#include <utility>
 #include <vector>
 
 #include "craft.h"
@@ -13,6 +16,7 @@ struct craft_layer_plan {
     std::vector<int32_t> slot_expert;    // [S]
     std::vector<int32_t> rank_slot_off;  // [D+1]
     std::vector<int64_t> rank_load;      // [D]
+    std::vector<int64_t> expert_load;    // [E] profiled load summed over batches
     int64_t est_max_rank_load = 0;
     double est_balancedness = 1.0;
 };
@@ -34,6 +38,8 @@ struct craft_plan {
     int32_t auto_R = 0;                  // replication factor picked in automatic mode
     std::mutex reg_mutex;
     std::vector<craft_table_reg> regs;   // device table buffers filled from this plan
+    // FFN row-tile heights chosen for (layer, rank, T, k, H, I): fragments for gate/up, down
+    std::map<std::array<int64_t, 6>, std::pair<int32_t, int32_t>> tile_cache;
 };
 
 // Device tables of one (layer, rank): a header followed by int32 arrays, all offsets in

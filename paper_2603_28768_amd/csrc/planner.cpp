@@ -390,6 +390,7 @@ craft_status craft_plan(const craft_plan_params *pp, craft_plan_t **out) {
                 lp.rank_slot_off.push_back((int32_t)lp.slot_expert.size());
             }
             lp.rank_load = pl.load;
+            lp.expert_load.assign(ws.begin() + (size_t)l * E, ws.begin() + (size_t)(l + 1) * E);
             int64_t mx = 0, sum = 0;
             for (int64_t v : pl.load) { mx = std::max(mx, v); sum += v; }
             lp.est_max_rank_load = mx;

@@ -216,3 +216,29 @@ def test_stack_shape_three_planners_side_by_side():
     auto = binding.Plan(W, D, 16 * D, objective=1, auto_r=True)
     R = auto.benefit()["auto_R"]
     assert 1 <= R <= 16 and auto.summary()["total_replicas"] == R * D
+
+
+def test_ffn_tile_heights_query():
+    # host-side choice of the grouped-GEMM row-tile height; no device work
+    lib = binding.lib()
+    g = np.random.default_rng(3)
+    W = g.multinomial(8 * 4096, synth.popularity(128, 1.0, 2, 0), size=(4, 1)).astype(np.int64)
+    plan = binding.Plan(W, 8, 8)
+    a = binding.FwdArgs()
+    a.dtype, a.T, a.H, a.I, a.k = 1, 4096, 4096, 1536, 8
+    gu, dn = ctypes.c_int32(), ctypes.c_int32()
+    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 0, ctypes.byref(a), gu, dn) == 0
+    assert (gu.value, dn.value) == (128, 128)                  # row-major bf16 weights: fixed
+    a.w_gateup_packed = a.w_down_packed = 0x1000               # packed: chosen from the plan's loads
+    for rank in range(8):
+        assert lib.craft_moe_rank_forward_tiles(plan._h, 0, rank, ctypes.byref(a), gu, dn) == 0
+        assert gu.value % 32 == 0 and 128 <= gu.value <= 256
+        assert dn.value % 32 == 0 and 128 <= dn.value <= 256
+        first = (gu.value, dn.value)
+        assert lib.craft_moe_rank_forward_tiles(plan._h, 0, rank, ctypes.byref(a), gu, dn) == 0
+        assert (gu.value, dn.value) == first                   # kept with the plan
+    a.dtype = 0
+    a.w_gateup_packed = a.w_down_packed = None
+    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 0, ctypes.byref(a), gu, dn) == 0
+    assert (gu.value, dn.value) == (32, 32)
+    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 9, ctypes.byref(a), gu, dn) == -1
