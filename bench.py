@@ -15,6 +15,7 @@ Prints one JSON line: tokens/s of the layer, plus
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -197,6 +198,32 @@ def copy_calibration(args):
                           unit="GB/s", bytes_read=n, bytes_written=n, ms_per_step=ms)), flush=True)
 
 
+# HBM traffic of the gate/up kernel per launch from rocprofv3 counters (profiles/
+# rank_forward_qwen3_hbm_traffic.txt): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, scaled by
+# what the same counters read for a plain 256 MiB copy (x2.0 and x1.0).  The figure belongs to
+# the kernel as it was when the counters were taken: it is reported only while the sources
+# that shape that kernel still hash to the recorded value.
+TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
+TRAFFIC = {"qwen3": dict(fetch_kib=254646.6, write_kib=23007.5, fetch_scale=2.0, write_scale=1.0,
+                         sources_sha256="66a04796abf9bb75be059564ea8106a32fbf75e223dd92dd33e6d71a1cbcbd8c")}
+
+
+def kernel_sources_sha256():
+    h = hashlib.sha256()
+    csrc = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2603_28768_amd", "csrc")
+    for name in TRAFFIC_SOURCES:
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(cfg_name, packed):
+    t = TRAFFIC.get(cfg_name)
+    if t is None or not packed or t["sources_sha256"] != kernel_sources_sha256():
+        return None
+    return (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0
+
+
 def plan_curves(args):
     """Balancedness against replica budget on the stack-shaped loads (58 layers x 256
     experts, 32 ranks, per-layer Zipf exponents in [0.6, 1.6]) for the three allocation rules
@@ -289,13 +316,14 @@ def main():
     gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
     tfs = gu_flops / (gu_ms * 1e-3) / 1e12
     flop_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+    traffic = measured_traffic(cfg.name, not args.unpacked and cfg.dtype == "bf16")   # bytes per launch
     t_hbm, t_mfma = gu_bytes / (HBM_PEAK_GBS * 1e9), gu_flops / (flop_peak * 1e12)
     if t_hbm >= t_mfma:
         roof = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=gbs / HBM_PEAK_GBS, traffic=None)
+                    frac=gbs / HBM_PEAK_GBS, traffic=traffic)
     else:
         roof = dict(bound="mfma" if cfg.dtype == "bf16" else "alu", achieved=tfs, peak=flop_peak,
-                    unit="TFLOP/s", frac=tfs / flop_peak, traffic=None)
+                    unit="TFLOP/s", frac=tfs / flop_peak, traffic=traffic)
     roof.update(kernel="grouped gate/up GEMM + SwiGLU", avg_ms=gu_ms,
                 launches=times["gateup"]["launches"], algorithmic_bytes=gu_bytes,
                 algorithmic_flops=gu_flops, hbm_frac=gbs / HBM_PEAK_GBS, flop_frac=tfs / flop_peak,
