@@ -205,7 +205,7 @@ def copy_calibration(args):
 # that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
 TRAFFIC = {"qwen3": dict(fetch_kib=254646.6, write_kib=23007.5, fetch_scale=2.0, write_scale=1.0,
-                         sources_sha256="66a04796abf9bb75be059564ea8106a32fbf75e223dd92dd33e6d71a1cbcbd8c")}
+                         sources_sha256="8ef1083cf33df88720c89ca0819f125b915346f6e63d56fc9fa723bc2461e246")}
 
 
 def kernel_sources_sha256():

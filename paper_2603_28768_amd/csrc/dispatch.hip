@@ -40,86 +40,102 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum
     return before + inc - v;
 }
 
-// One workgroup per 64 experts.  Wave w owns a contiguous range of blocks; a lane owns one
-// expert.  Each wave sums its range, the waves' sums are prefix-combined through LDS, and
-// the per-block counts are rewritten as exclusive prefixes.  The workgroup that finishes
-// last (ticket counter) derives everything that needs all counts: rows per slot, slot
-// offsets, the rank's row count and the row-tile table of the grouped GEMMs.
+// One workgroup per 64 experts (or a single workgroup for all of them when there are few
+// token blocks).  Wave w owns a contiguous range of blocks; a lane owns one expert.  Each
+// wave sums its range, the waves' sums are prefix-combined through LDS, and the per-block
+// counts are rewritten as exclusive prefixes.  The workgroup that finishes last (ticket
+// counter; trivially the only one) derives everything that needs all counts: rows per slot,
+// slot offsets, the rank's row count and the row-tile tables of the grouped GEMMs.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     __shared__ int32_t part[kScanWaves][64];
     __shared__ int32_t wsum[kScanWaves];
     __shared__ int32_t cnt_lds[1024];
     __shared__ int32_t last_flag;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int e = blockIdx.x * 64 + lane;
     const int rows_per_wave = (a.NB + kScanWaves - 1) / kScanWaves;
     const int b0 = min(a.NB, wave * rows_per_wave), b1 = min(a.NB, b0 + rows_per_wave);
+    // Launched as one workgroup (few blocks of tokens), it walks over the groups of 64 experts
+    // itself and goes straight on to the tail: no ticket, no device-wide fences.
+    const bool single = gridDim.x == 1;
+    const int groups = (a.E + 63) / 64;
 
-    // the common case keeps a wave's block counts in registers between the two passes
-    constexpr int kKeep = 16;
-    int32_t keep[kKeep];
-    int32_t sum = 0;
-    if (e < a.E) {
-        if (rows_per_wave <= kKeep) {
+    for (int grp = single ? 0 : (int)blockIdx.x; grp < (single ? groups : (int)blockIdx.x + 1); ++grp) {
+        const int e = grp * 64 + lane;
+        // the common case keeps a wave's block counts in registers between the two passes
+        constexpr int kKeep = 16;
+        int32_t keep[kKeep];
+        int32_t sum = 0;
+        if (e < a.E) {
+            if (rows_per_wave <= kKeep) {
 #pragma unroll
-            for (int i = 0; i < kKeep; ++i) {
-                keep[i] = b0 + i < b1 ? a.hist[(int64_t)(b0 + i) * a.E + e] : 0;
-                sum += keep[i];
-            }
-        } else {
-            for (int b = b0; b < b1; ++b) sum += a.hist[(int64_t)b * a.E + e];
-        }
-    }
-    part[wave][lane] = sum;
-    __syncthreads();
-    int32_t before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < kScanWaves; ++w) {
-        const int32_t v = part[w][lane];
-        if (w < wave) before += v;
-        total += v;
-    }
-    if (e < a.E) {
-        int32_t run = before;
-        if (rows_per_wave <= kKeep) {
-#pragma unroll
-            for (int i = 0; i < kKeep; ++i)
-                if (b0 + i < b1) { a.hist[(int64_t)(b0 + i) * a.E + e] = run; run += keep[i]; }
-        } else {
-            for (int b = b0; b < b1; ++b) {
-                int32_t *p = a.hist + (int64_t)b * a.E + e;
-                const int32_t v = *p;
-                *p = run;
-                run += v;
+                for (int i = 0; i < kKeep; ++i) {
+                    keep[i] = b0 + i < b1 ? a.hist[(int64_t)(b0 + i) * a.E + e] : 0;
+                    sum += keep[i];
+                }
+            } else {
+                for (int b = b0; b < b1; ++b) sum += a.hist[(int64_t)b * a.E + e];
             }
         }
-        if (wave == 0) {
-            a.counts[e] = total;
-            if (a.user_counts) a.user_counts[e] = total;
+        part[wave][lane] = sum;
+        __syncthreads();
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kScanWaves; ++w) {
+            const int32_t v = part[w][lane];
+            if (w < wave) before += v;
+            total += v;
         }
+        if (e < a.E) {
+            int32_t run = before;
+            if (rows_per_wave <= kKeep) {
+#pragma unroll
+                for (int i = 0; i < kKeep; ++i)
+                    if (b0 + i < b1) { a.hist[(int64_t)(b0 + i) * a.E + e] = run; run += keep[i]; }
+            } else {
+                for (int b = b0; b < b1; ++b) {
+                    int32_t *p = a.hist + (int64_t)b * a.E + e;
+                    const int32_t v = *p;
+                    *p = run;
+                    run += v;
+                }
+            }
+            if (wave == 0) {
+                a.counts[e] = total;
+                if (a.user_counts) a.user_counts[e] = total;
+                if (single) cnt_lds[e] = total;
+            }
+        }
+        __syncthreads();                   // `part` is reused by the next group
     }
 
-    // publish, then take a ticket
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const int32_t ticket = atomicAdd(&a.ctrl[CTRL_TICKET], 1);
-        last_flag = ticket == (int32_t)gridDim.x - 1;
+    if (!single) {
+        // publish, then take a ticket
+        __threadfence();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const int32_t ticket = atomicAdd(&a.ctrl[CTRL_TICKET], 1);
+            last_flag = ticket == (int32_t)gridDim.x - 1;
+        }
+        __syncthreads();
+        if (!last_flag) return;
+        __threadfence();
     }
-    __syncthreads();
-    if (!last_flag) return;
-    __threadfence();
 
     const craft_tables_header *hdr = reinterpret_cast<const craft_tables_header *>(a.tables);
     const int32_t *copies = a.tables + hdr->off_copies;
     const int32_t *slot_expert = a.tables + hdr->off_slot_expert;
     const int32_t *slot_copy = a.tables + hdr->off_slot_copy;
-    for (int32_t i = threadIdx.x; i < a.E; i += kScanThreads)
-        cnt_lds[i] = __hip_atomic_load(a.counts + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (!single)
+        for (int32_t i = threadIdx.x; i < a.E; i += kScanThreads)
+            cnt_lds[i] = __hip_atomic_load(a.counts + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
 
     // rows of slot p: tokens i < n of its expert with i mod c == q.  Slots are taken in
     // chunks of one per thread; `carry` is the running offset across chunks.
+    // The rank's own slot rows and the two offsets that bound its rows stay in LDS: reading
+    // them back from global memory would be two more dependent round trips in this serial tail.
+    __shared__ int32_t rank_slot_rows[1024];
+    __shared__ int32_t bound_pos[2];
     int32_t carry = 0, lo_pos = 0, hi_pos = 0;
     for (int32_t base = 0; base < a.S; base += kScanThreads) {
         const int32_t p = base + threadIdx.x;
@@ -136,6 +152,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
             a.slot_off[p] = off;
             if (a.user_slot_cnt) a.user_slot_cnt[p] = r;
             if (a.user_slot_off) a.user_slot_off[p] = off;
+            if (p >= a.s_lo && p < a.s_hi) rank_slot_rows[p - a.s_lo] = r;
+            if (p == a.s_lo) bound_pos[0] = off;
+            if (p == a.s_hi) bound_pos[1] = off;
         }
         carry += chunk_total;
     }
@@ -143,9 +162,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         a.slot_off[a.S] = carry;
         if (a.user_slot_off) a.user_slot_off[a.S] = carry;
     }
-    __syncthreads();                       // this workgroup's slot_off stores, visible to itself
-    lo_pos = a.s_lo < a.S ? a.slot_off[a.s_lo] : carry;
-    hi_pos = a.s_hi < a.S ? a.slot_off[a.s_hi] : carry;
+    __syncthreads();
+    lo_pos = a.s_lo < a.S ? bound_pos[0] : carry;
+    hi_pos = a.s_hi < a.S ? bound_pos[1] : carry;
     // this rank's rows; refuse the batch when they exceed the staging buffers
     const int32_t rank_rows = hi_pos - lo_pos;
     const bool ovf = (int64_t)rank_rows > a.max_rows;
@@ -153,14 +172,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     // Order the rank's slots by rows, busiest first (ties: lower slot), so the tile list
     // starts with the matrix-bound tiles and ends with the cheap weight-streaming ones.
     __shared__ int32_t sorted_rows[1024];
-    __syncthreads();
-    for (int32_t sl = threadIdx.x; sl < nslots; sl += kScanThreads) cnt_lds[sl] = a.slot_cnt[a.s_lo + sl];
-    __syncthreads();
     for (int32_t sl = threadIdx.x; sl < nslots; sl += kScanThreads) {
-        const int32_t mine = cnt_lds[sl];
+        const int32_t mine = rank_slot_rows[sl];
         int32_t pos = 0;
         for (int32_t j = 0; j < nslots; ++j) {
-            const int32_t other = cnt_lds[j];
+            const int32_t other = rank_slot_rows[j];
             pos += (other > mine || (other == mine && j < sl)) ? 1 : 0;
         }
         a.order[pos] = sl;
@@ -220,7 +236,8 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a) {
 }  // namespace
 
 hipError_t launch_scan(const ScanArgs &a, hipStream_t s) {
-    const unsigned blocks = (unsigned)((a.E + 63) / 64);
+    // few token blocks: one workgroup does everything; many: one workgroup per 64 experts
+    const unsigned blocks = a.NB <= 16 * kScanWaves ? 1u : (unsigned)((a.E + 63) / 64);
     hipLaunchKernelGGL(scan_kernel, dim3(blocks), dim3(kScanThreads), 0, s, a);
     return hipGetLastError();
 }
