@@ -88,5 +88,18 @@ static __device__ __forceinline__ uint32_t bf16_rne(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 static __device__ __forceinline__ float silu(float g) { return g / (1.0f + __expf(-g)); }
+// The same with the hardware reciprocal (1 ulp) instead of a correctly rounded division: the
+// result is rounded to bf16 right after.
+static __device__ __forceinline__ float silu_fast(float g) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+}
+// Two fp32 values to a pair of bf16 (round to nearest even) in one 32-bit word, low half first:
+// a single v_cvt_pk_bf16_f32 on gfx950.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+static __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 
 }  // namespace craft

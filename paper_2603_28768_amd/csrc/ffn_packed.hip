@@ -193,27 +193,43 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     }
 
     // epilogue.  Accumulator element v of lane l belongs to weight row
-    // (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of fragment g.
+    // (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of fragment g: for each
+    // block vg of 8 output columns a lane holds 4 of them and lane l ^ 32 the other 4 of the same
+    // row.  Two blocks at a time, the halves of the wave trade pieces (v_permlane32_swap: the
+    // upper half of the first operand against the lower half of the second), after which the
+    // lower half owns all 8 columns of the first block and the upper half those of the second:
+    // 16-byte stores, half as many as 8-byte ones would be.
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
+    const bool upper = lane >= 32;
 #pragma unroll
     for (int n = 0; n < NG; ++n) {
         const int cbase = (group0 + n) * GC;
 #pragma unroll
         for (int g = 0; g < NXF; ++g) {
             const int m = g * 32 + (lane & 31);
-            if (m >= t.rows) continue;
-            unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + m - lo_pos) * N;
+            unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
             // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
 #pragma unroll
-            for (int vg = 0; vg < (GATEUP ? 2 : 4); ++vg) {
-                const int col = cbase + vg * 8 + (lane >> 5) * 4;
-                if (col >= N) continue;
-                uint32_t h[4];
+            for (int vg = 0; vg < (GATEUP ? 2 : 4); vg += 2) {
+                uint32_t piece[2][2];
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    h[c] = GATEUP ? bf16_rne(silu(acc[n][g][vg * 4 + c]) * acc[n][g][8 + vg * 4 + c])
-                                  : bf16_rne(acc[n][g][vg * 4 + c]);
-                *reinterpret_cast<uint2 *>(orow + col) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                for (int b = 0; b < 2; ++b) {
+                    float h[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c]) * acc[n][g][8 + (vg + b) * 4 + c]
+                                      : acc[n][g][(vg + b) * 4 + c];
+                    piece[b][0] = bf16_pair(h[0], h[1]);
+                    piece[b][1] = bf16_pair(h[2], h[3]);
+                }
+                const auto s0 = __builtin_amdgcn_permlane32_swap(piece[0][0], piece[1][0], false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(piece[0][1], piece[1][1], false, false);
+                const int col = cbase + (vg + (upper ? 1 : 0)) * 8;
+                if (m < t.rows && col < N) {
+                    u32x4_t v;
+                    v[0] = s0[0]; v[1] = s1[0]; v[2] = s0[1]; v[3] = s1[1];
+                    *reinterpret_cast<u32x4_t *>(orow + col) = v;
+                }
             }
         }
     }
