@@ -201,7 +201,19 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         if (threadIdx.x == 0) mt_out[nslots] = mcarry;
         mtotal[kind] = mcarry;
     }
+    // the busy and the live slots are prefixes of the busiest-first order
+    __shared__ int32_t prefix_len[2];
+    if (threadIdx.x == 0) prefix_len[0] = prefix_len[1] = 0;
+    __syncthreads();
+    for (int32_t pos = threadIdx.x; pos < nslots; pos += kScanThreads) {
+        const int32_t r = sorted_rows[pos], nxt = pos + 1 < nslots ? sorted_rows[pos + 1] : 0;
+        if (r > kColdRows && nxt <= kColdRows) prefix_len[0] = pos + 1;
+        if (r > 0 && nxt <= 0) prefix_len[1] = pos + 1;
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
+        a.ctrl[CTRL_HOT_SLOTS] = ovf ? 0 : prefix_len[0];
+        a.ctrl[CTRL_LIVE_SLOTS] = ovf ? 0 : prefix_len[1];
         a.ctrl[CTRL_ROWS] = rank_rows;
         a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
         a.ctrl[CTRL_MTILES] = mtotal[0];

@@ -41,7 +41,8 @@ namespace {
 // row fragments, shallower where the accumulators need the registers and each step carries
 // enough MFMA work to cover the latency.
 constexpr int ring_depth(int nxf) { return nxf >= 3 ? 8 : 16; }
-constexpr int NG = 2;             // column groups per wave
+constexpr int NG = 2;             // column groups per wave in a full-width tile (1 in a half-width one)
+constexpr int kPackGroups = 8;    // the packed stream is padded to whole full-width tiles
 constexpr int XROWB = 64 * 2 + 16;
 constexpr int XSTAGEB = kBM_packed * XROWB;
 
@@ -49,32 +50,32 @@ typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 
-// One 16-wide contraction step of NG x NXF MFMAs.  A wave is alone on its SIMD, so whatever
+// One 16-wide contraction step of NGT x NXF MFMAs (NGT column groups per wave).  A wave is alone on its SIMD, so whatever
 // it issues between two MFMAs delays the second one unless it fits into the 32 cycles the
 // first one keeps the matrix pipeline busy: memory operations are therefore dealt out one or
 // two per MFMA, and a scheduling barrier after each MFMA pins that order.
 //   MFMA j < NXF        : + LDS read of fragment j of the FOLLOWING step into XN (a whole step
 //                         of matrix work covers its latency; this step runs on XC)
-//   MFMA NXF + i        : + (PHASE 0/1, the first two steps of a slab) activation row chunk i
+//   last group's MFMA i : + (PHASE 0/1, the first two steps of a slab) activation row chunk i
 //                         of the next slab goes from XR to LDS stage `nxt`, and the same
 //                         registers are requested again for the slab after it
-//   MFMA NXF, 2 NXF - 1 : + refill of the weight ring slot each column group has just used
-template <int NXF, int R, int PW, int PHASE>
+//   a group's last MFMA : + refill of the weight ring slot that group has just used
+template <int NXF, int NGT, int R, int PW, int PHASE>
 __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, wstream_t wp,
-                                            int64_t wstride, bf16x8_t (&wq)[NG][PW],
+                                            int64_t wstride, bf16x8_t (&wq)[NGT][PW],
                                             const bf16x8_t (&XC)[NXF], bf16x8_t (&XN)[NXF],
-                                            f32x16_t (&acc)[NG][NXF], unsigned char *xstage,
+                                            f32x16_t (&acc)[NGT][NXF], unsigned char *xstage,
                                             u32x4_t (&XR)[NXF], const unsigned short *const (&xp)[NXF],
                                             int koff) {
     constexpr int HALF = (NXF + 1) / 2;
     const int64_t nxt = min(step + PW, ksteps - 1) * wstride;
 #pragma unroll
-    for (int n = 0; n < NG; ++n)
+    for (int n = 0; n < NGT; ++n)
 #pragma unroll
         for (int g = 0; g < NXF; ++g) {
             acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], XC[g], acc[n][g], 0, 0, 0);
             if (n == 0) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
-            if (n == 1 && PHASE < 2) {
+            if (n == NGT - 1 && PHASE < 2) {
                 const int i = PHASE * HALF + g;
                 if (g < HALF && i < NXF) {
                     *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
@@ -92,26 +93,26 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
 // ahead is requested from global memory into the same registers; the last step already
 // fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
 // enough: a stage is rewritten a full slab after its last reader has passed a barrier.
-template <int NXF, int U, int PW>
+template <int NXF, int NGT, int U, int PW>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
                                             wstream_t wp, int64_t wstride,
-                                            const unsigned short *const (&xp)[NXF], bf16x8_t (&wq)[NG][PW],
+                                            const unsigned short *const (&xp)[NXF], bf16x8_t (&wq)[NGT][PW],
                                             u32x4_t (&XR)[NXF], bf16x8_t (&X0)[NXF], bf16x8_t (&X1)[NXF],
-                                            f32x16_t (&acc)[NG][NXF]) {
+                                            f32x16_t (&acc)[NGT][NXF]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
     const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, (U * 4 + 0) % PW, PW, 0>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, (U * 4 + 1) % PW, PW, 1>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 0) % PW, PW, 0>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 1) % PW, PW, 1>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
     __syncthreads();
-    packed_step<NXF, (U * 4 + 2) % PW, PW, 2>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, (U * 4 + 3) % PW, PW, 2>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 2) % PW, PW, 2>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 3) % PW, PW, 2>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
 }
 
 // One tile with NXF live 32-row activation fragments.
-template <bool GATEUP, int NXF>
+template <bool GATEUP, int NXF, int NGT>
 __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, unsigned char *smem,
                                             int K, int N, int ngroups, int nk4, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
@@ -120,12 +121,12 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     const int lr = tid >> 3, kc = tid & 7;
     const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
     const int ksteps = nk4 * 16;
-    const int group0 = t.n0 / GC + wave * NG;      // this wave's first column group
+    const int group0 = t.n0 / GC + wave * NGT;     // this wave's first column group
     const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
     // step-major stream: the fragments of all column groups for one step are adjacent.
-    // The packed buffer holds a multiple of NG*4 groups (zero padded), so every wave of a
-    // tile has a stream to read even past the last real column.
-    const int groups_padded = (ngroups + NG * 4 - 1) / (NG * 4) * (NG * 4);
+    // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
+    // of a tile has a stream to read even past the last real column.
+    const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
     wstream_t wp = (wstream_t)wbase + (int64_t)group0 * 64 + lane;
     const int64_t wstride = (int64_t)groups_padded * 64;
     const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
@@ -139,9 +140,9 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
         else xp[i] = xin + (int64_t)(pos - lo_pos) * K;
     }
 
-    f32x16_t acc[NG][NXF];
+    f32x16_t acc[NGT][NXF];
 #pragma unroll
-    for (int n = 0; n < NG; ++n)
+    for (int n = 0; n < NGT; ++n)
 #pragma unroll
         for (int g = 0; g < NXF; ++g)
 #pragma unroll
@@ -150,14 +151,14 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     // Request order: half the weight ring, the first two activation slabs, the other half of
     // the ring.  The second slab is then followed by as many weight requests as in the loop,
     // so the in-order load counter need not be drained when the loop is entered.
-    bf16x8_t wq[NG][PW];
+    bf16x8_t wq[NGT][PW];
     u32x4_t xr[NXF];
     {
         u32x4_t xfirst[NXF];
 #pragma unroll
         for (int j = 0; j < PW / 2; ++j)
 #pragma unroll
-            for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
         const int k0 = min(kc * 8, K - 8), k1 = min(64 + kc * 8, K - 8);
 #pragma unroll
         for (int i = 0; i < NXF; ++i) xfirst[i] = *(xchunk_t)(xp[i] + k0);
@@ -167,7 +168,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
 #pragma unroll
         for (int j = PW / 2; j < PW; ++j)
 #pragma unroll
-            for (int n = 0; n < NG; ++n) wq[n][j] = wp[j * wstride + n * 64];
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NXF; ++i)
@@ -185,10 +186,10 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
         unsigned char *s0 = smem + st * XSTAGEB;
         unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
         unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
-        packed_slab<NXF, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
         st = (st + 1) % 3;
     }
 
@@ -202,7 +203,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
 #pragma unroll
-    for (int n = 0; n < NG; ++n) {
+    for (int n = 0; n < NGT; ++n) {
         const int cbase = (group0 + n) * GC;
 #pragma unroll
         for (int g = 0; g < NXF; ++g) {
@@ -250,23 +251,42 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     const int ngroups = (N + GC - 1) / GC;
     const int nt = (N + BN - 1) / BN;
     const int nk4 = (K + 255) / 256;               // groups of four 64-wide slabs
-    const int64_t total = (int64_t)mt_start[a.nslots] * nt;
+    // The tile list: the busy slots' tiles (row-tiles x nt column tiles each, found through
+    // mt_start), then the cold slots' (one row-tile, 2 nt half-width column tiles each).
+    const int32_t hot = a.ctrl[CTRL_HOT_SLOTS], live = a.ctrl[CTRL_LIVE_SLOTS];
+    const int64_t hot_tiles = (int64_t)mt_start[hot] * nt;
+    const int64_t total = hot_tiles + (int64_t)(live - hot) * 2 * nt;
     const int32_t lo_pos = a.slot_off[a.s_lo];
     const int32_t fmax = GATEUP ? a.frags_gu : a.frags_dn;
     int32_t *counter = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
 
     int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
-        const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
-        switch ((t.rows + 31) >> 5) {              // live 32-row fragments of this tile
-            case 1: packed_tile<GATEUP, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 2: packed_tile<GATEUP, 2>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 3: packed_tile<GATEUP, 3>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 4: packed_tile<GATEUP, 4>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 5: packed_tile<GATEUP, 5>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 6: packed_tile<GATEUP, 6>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            case 7: packed_tile<GATEUP, 7>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-            default: packed_tile<GATEUP, 8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+        if (w < hot_tiles) {
+            const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
+            switch ((t.rows + 31) >> 5) {          // live 32-row fragments of this tile
+                case 1: packed_tile<GATEUP, 1, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 2: packed_tile<GATEUP, 2, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 3: packed_tile<GATEUP, 3, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 4: packed_tile<GATEUP, 4, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 5: packed_tile<GATEUP, 5, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 6: packed_tile<GATEUP, 6, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 7: packed_tile<GATEUP, 7, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                default: packed_tile<GATEUP, 8, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            }
+        } else {
+            const int64_t cw = w - hot_tiles;
+            const int32_t pos = hot + (int32_t)(cw / (2 * nt));
+            Tile t;
+            t.slot = small ? tt.order[pos] : a.order[pos];
+            t.pos0 = small ? tt.slot_off[t.slot] : a.slot_off[a.s_lo + t.slot];
+            t.rows = (small ? tt.slot_off[t.slot + 1] : a.slot_off[a.s_lo + t.slot + 1]) - t.pos0;
+            t.m0 = 0;
+            t.n0 = (int32_t)(cw % (2 * nt)) * (BN / 2);
+            if (t.n0 < N) {                        // the last half may lie past the matrix
+                if (t.rows <= 32) packed_tile<GATEUP, 1, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos);
+                else packed_tile<GATEUP, 2, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos);
+            }
         }
         if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
         __syncthreads();
@@ -307,7 +327,7 @@ hipError_t launch_packed(const FfnArgs &a, hipStream_t s) {
     const int N = GATEUP ? a.I : a.H;
     const int bn = GATEUP ? 128 : 256;
     const int64_t nt = (N + bn - 1) / bn;
-    const int64_t bound = (a.max_rows / (32 * std::abs(GATEUP ? a.frags_gu : a.frags_dn)) + a.nslots) * nt;
+    const int64_t bound = (a.max_rows / (32 * std::abs(GATEUP ? a.frags_gu : a.frags_dn)) + 2 * a.nslots) * nt;
     int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu);
     grid = std::max<int64_t>(8, (grid + 7) / 8 * 8);
     hipLaunchKernelGGL(ffn_packed_kernel<GATEUP>, dim3((unsigned)grid), dim3(256), 0, s, a);

@@ -110,6 +110,15 @@ double ffn_makespan(const std::vector<double> &slot_rows, int32_t frags, bool ev
     for (double r : slot_rows) {
         const int64_t F = (int64_t)((r + 31.0) / 32.0);
         if (F <= 0) continue;
+        if (r <= (double)kColdRows) {              // cold slot: half-width tiles, about half the cost
+            for (int64_t n = 0; n < 2 * nt; ++n) {
+                const double t = free_at.top() + 4.0 + 0.5 * (fixed_us + frag_us * (double)F);
+                free_at.pop();
+                free_at.push(t);
+                end = std::max(end, t);
+            }
+            continue;
+        }
         const int64_t m = (F + frags - 1) / frags;
         for (int64_t n = 0; n < nt; ++n)
             for (int64_t i = 0; i < m; ++i) {

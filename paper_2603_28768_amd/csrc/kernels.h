@@ -17,7 +17,15 @@ constexpr int kTokPerBlock = 32;
 // Control words at the start of the workspace.
 enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
        CTRL_WORK_GATEUP = 4, CTRL_WORK_DOWN = 5,   // dynamic tile counters of the two GEMMs
+       CTRL_HOT_SLOTS = 6,                         // slots of the rank with more than kColdRows rows
+       CTRL_LIVE_SLOTS = 7,                        // slots of the rank with any rows
        CTRL_WORDS = 16 };
+
+// A slot with at most this many rows is "cold": its tiles do next to no matrix work and are
+// bound by streaming the weights.  The packed FFN cuts their column tiles in half (twice as
+// many, half as long), because what the tail of a launch costs is the length of a cold tile
+// and the aggregate weight bandwidth grows with the number of CUs streaming at once.
+constexpr int kColdRows = 64;
 
 // Most 32-row fragments a row-tile of the grouped GEMMs may have (the tile table is built for
 // a height chosen per launch, up to these).
