@@ -227,6 +227,8 @@ craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void 
  *   max_rows rows the staging buffers are sized for.  0 = the worst case
  *            T * min(k, s).  If the batch routes more rows than this to the rank the
  *            forward does no FFN work, zero-fills out and sets the overflow flag.
+ *   tile_rows_gateup, tile_rows_down  tuning knobs of the packed FFN, normally 0: see
+ *            craft_moe_rank_forward_tiles for what the library picks by itself
  *   workspace DEVICE, 256-byte aligned, at least craft_moe_rank_forward_workspace() bytes.
  *            Forwards that share a workspace must be ordered on one stream.
  * Alignment: x, out and all weight matrices 16-byte aligned; H % 8 == 0 and I % 8 == 0
@@ -254,6 +256,8 @@ typedef struct {
     int32_t *slot_cnt;
     int32_t *slot_off;
     int64_t max_rows;
+    int32_t tile_rows_gateup;  /* packed weights only: rows per row-tile of the gate/up GEMM, */
+    int32_t tile_rows_down;    /* of the down GEMM: 128, 160, .., 256; 0 = chosen by the library */
     const void *tables;        /* from craft_plan_tables_upload */
     void *workspace;
     size_t workspace_bytes;

@@ -34,7 +34,8 @@ class FwdArgs(ctypes.Structure):
                 ("w_up", c_vp), ("w_down", c_vp), ("w_gateup_packed", c_vp), ("w_down_packed", c_vp),
                 ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
                 ("dest", c_vp), ("src", c_vp), ("counts", c_vp), ("slot_cnt", c_vp),
-                ("slot_off", c_vp), ("max_rows", c_i64), ("tables", c_vp), ("workspace", c_vp),
+                ("slot_off", c_vp), ("max_rows", c_i64), ("tile_rows_gateup", c_i32),
+                ("tile_rows_down", c_i32), ("tables", c_vp), ("workspace", c_vp),
                 ("workspace_bytes", c_sz)]
 
 

@@ -155,6 +155,13 @@ std::pair<int32_t, int32_t> choose_tile_frags(const craft_plan_t *plan, int32_t 
         // per-tile device timestamps at K = 4096 and 7168 (gate/up) and 1536 and 2048 (down)
         const double fixed_us = kind == 0 ? 20.0 + 0.0055 * (double)K : 21.0 + 0.0020 * (double)K;
         const double frag_us = kind == 0 ? 1.5 + 0.00182 * (double)K : 0.1 + 0.00234 * (double)K;
+        // Only where the busy slots' tiles make up a round or two does their count decide the
+        // time; over many rounds the tallest tile (most reuse per weight fragment, fewest
+        // fixed costs) wins by itself, and there the model is not trusted to say otherwise.
+        int64_t tall_tiles = 0;
+        for (double r : rows)
+            if (r > (double)kColdRows) tall_tiles += (((int64_t)((r + 31.0) / 32.0) + kFragsPacked - 1) / kFragsPacked) * nt;
+        if (tall_tiles > 2 * (int64_t)cus) continue;
         double best_t = 0.0;
         for (int32_t f = kFragsPacked; f >= 4; --f)
             for (int even = 0; even < 2; ++even) {
@@ -179,7 +186,10 @@ std::pair<int32_t, int32_t> tile_frags_for(const craft_plan_t *plan, int32_t lay
     if (it == p->tile_cache.end())
         it = p->tile_cache.emplace(key, choose_tile_frags(plan, layer, rank, a->T, a->k, a->H, a->I,
                                                            cached_num_cu())).first;
-    return it->second;
+    std::pair<int32_t, int32_t> f = it->second;
+    if (a->tile_rows_gateup) f.first = a->tile_rows_gateup / 32;      // the caller's own choice
+    if (a->tile_rows_down) f.second = a->tile_rows_down / 32;
+    return f;
 }
 
 craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a) {
@@ -187,6 +197,8 @@ craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, co
     if (a->dtype != CRAFT_F32 && a->dtype != CRAFT_BF16) return CRAFT_EINVAL;
     if (a->T < 0 || a->H <= 0 || a->I <= 0 || a->k <= 0 || a->k > 64 || a->k > plan->E) return CRAFT_EINVAL;
     if (plan->E > 1024 || a->max_rows < 0) return CRAFT_EINVAL;
+    for (int32_t r : {a->tile_rows_gateup, a->tile_rows_down})
+        if (r != 0 && (r % 32 || r < 128 || r > 256)) return CRAFT_EINVAL;
     if (a->T * (int64_t)a->k >= ((int64_t)1 << 31)) return CRAFT_EINVAL;
     const int unit = a->dtype == CRAFT_BF16 ? 8 : 4;
     if (a->H % unit || a->I % unit) return CRAFT_EINVAL;
