@@ -56,9 +56,10 @@ typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 // two per MFMA, and a scheduling barrier after each MFMA pins that order.
 //   MFMA j < NXF        : + LDS read of fragment j of the FOLLOWING step into XN (a whole step
 //                         of matrix work covers its latency; this step runs on XC)
-//   last group's MFMA i : + (PHASE 0/1, the first two steps of a slab) activation row chunk i
-//                         of the next slab goes from XR to LDS stage `nxt`, and the same
-//                         registers are requested again for the slab after it
+//   last group's MFMAs  : + (PHASE 0/1, the first two steps of a slab) an activation row chunk
+//                         of the next slab goes from XR to LDS stage `nxt` behind one MFMA, and
+//                         the same registers are requested again for the slab after it behind
+//                         the next MFMA
 //   a group's last MFMA : + refill of the weight ring slot that group has just used
 template <int NXF, int NGT, int R, int PW, int PHASE>
 __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, wstream_t wp,
@@ -76,10 +77,11 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
             acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], XC[g], acc[n][g], 0, 0, 0);
             if (n == 0) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
             if (n == NGT - 1 && PHASE < 2) {
-                const int i = PHASE * HALF + g;
-                if (g < HALF && i < NXF) {
-                    *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
-                    XR[i] = *(xchunk_t)(xp[i] + koff);
+                // chunk i: its LDS write behind an even MFMA, its new request behind the next one
+                const int i = PHASE * HALF + g / 2;
+                if (i < NXF && i < (PHASE + 1) * HALF) {
+                    if ((g & 1) == 0) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
+                    if ((g & 1) == 1 || g == NXF - 1) XR[i] = *(xchunk_t)(xp[i] + koff);
                 }
             }
             if (g == NXF - 1) wq[n][R] = wp[nxt + n * 64];
