@@ -44,6 +44,10 @@ def _load():
         lib.oracle_dispatch.argtypes = [vp, c_i64, c_i32, c_i32, vp, vp, vp, vp, vp]
         lib.oracle_ffn_rows.argtypes = [vp, c_i64, c_i32, c_i32, vp, vp, vp, vp]
         lib.oracle_combine.argtypes = [vp, c_i64, c_i64, vp, vp, c_i64, c_i32, c_i32, vp]
+        lib.oracle_quantize_e4m3.argtypes = [vp, c_i64, c_i64, vp, vp]
+        lib.oracle_quantize_e4m3.restype = ctypes.c_int
+        lib.oracle_e4m3_value.argtypes = [ctypes.c_uint8]
+        lib.oracle_e4m3_value.restype = ctypes.c_double
         for f in (lib.oracle_route, lib.oracle_expert_load, lib.oracle_dispatch,
                   lib.oracle_ffn_rows, lib.oracle_combine, lib.oracle_num_threads):
             f.restype = ctypes.c_int
@@ -113,6 +117,28 @@ def ffn_rows(X: np.ndarray, Wg: np.ndarray, Wu: np.ndarray, Wd: np.ndarray) -> n
     if rc:
         raise ValueError(f"oracle_ffn_rows failed ({rc})")
     return Y
+
+
+def e4m3_value(code: int) -> float:
+    return float(_load().oracle_e4m3_value(int(code)))
+
+
+def quantize_e4m3(W: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """(codes uint8 [rows][K], scale float32 [rows]) of a weight matrix, one scale per row."""
+    W = _c(W, np.float32)
+    rows, K = W.shape
+    codes = np.empty((rows, K), dtype=np.uint8)
+    scale = np.empty(rows, dtype=np.float32)
+    rc = _load().oracle_quantize_e4m3(_p(W), rows, K, _p(codes), _p(scale))
+    if rc:
+        raise ValueError(f"oracle_quantize_e4m3 failed ({rc})")
+    return codes, scale
+
+
+def dequantize_e4m3(codes: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """float64 [rows][K]: code value times the row's scale, exactly."""
+    table = np.array([e4m3_value(c) for c in range(256)], dtype=np.float64)
+    return table[codes] * scale.astype(np.float64)[:, None]
 
 
 def combine(Y: np.ndarray, lo: int, dest: np.ndarray, w: np.ndarray, T: int, k: int) -> np.ndarray:

@@ -20,6 +20,13 @@
  *   oracle_ffn_rows      Sec. 2.1: expert = up-projection, non-linearity,
  *                        down-projection (SwiGLU form: down(silu(gate x) * up x)).
  *   oracle_combine       Sec. 2.1: expert outputs aggregated into a weighted sum.
+ *   oracle_e4m3_value, oracle_quantize_e4m3
+ *                        not in the paper: 8-bit storage of expert weights (OCP FP8
+ *                        E4M3: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
+ *                        no infinities, S.1111.111 = NaN, largest finite 448), one
+ *                        scale per weight row.  Replication memory is what the paper
+ *                        trades against balance; halving the bytes of a replica is
+ *                        the adjacent lever.
  */
 #include <math.h>
 #include <stdint.h>
@@ -201,6 +208,50 @@ int oracle_combine(const double *Y, int64_t M, int64_t lo, const int32_t *dest, 
             const double *y = Y + (d - lo) * H;
             double wj = (double)w[t * k + j];
             for (int32_t h = 0; h < H; ++h) o[h] += wj * y[h];
+        }
+    }
+    return 0;
+}
+
+/* Value of an E4M3 code, from the format's definition: exponent field 0 is subnormal,
+ * mantissa / 8 * 2^-6; otherwise (1 + mantissa / 8) * 2^(exponent - 7).  NaN codes give NaN. */
+double oracle_e4m3_value(uint8_t code)
+{
+    const int sign = code >> 7, ex = (code >> 3) & 15, man = code & 7;
+    double v;
+    if (ex == 15 && man == 7) return NAN;
+    if (ex == 0) v = ldexp((double)man / 8.0, -6);
+    else v = ldexp(1.0 + (double)man / 8.0, ex - 7);
+    return sign ? -v : v;
+}
+
+/* Weight rows to E4M3 codes with one scale per row.
+ *   scale[r] = max_k |w[r][k]| / 448, computed in float (1 when the row is all zero);
+ *   code     = the E4M3 value nearest to the float quotient w / scale, ties to the even
+ *              mantissa, magnitudes beyond 448 saturating to 448 (cannot happen here but
+ *              is the rule), the sign kept (a negative value that rounds to zero keeps
+ *              its sign bit).
+ * The nearest value is found by looking at all 127 finite magnitudes: slow and obviously
+ * the definition.  Returns 0, or -1 on bad sizes. */
+int oracle_quantize_e4m3(const float *w, int64_t rows, int64_t K, uint8_t *codes, float *scale)
+{
+    if (rows < 0 || K <= 0) return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        const float *row = w + r * K;
+        float amax = 0.0f;
+        for (int64_t k = 0; k < K; ++k) { const float a = fabsf(row[k]); if (a > amax) amax = a; }
+        const float s = amax > 0.0f ? amax / 448.0f : 1.0f;
+        scale[r] = s;
+        for (int64_t k = 0; k < K; ++k) {
+            const float q = row[k] / s;                  /* float division, as stated */
+            const double a = fabs((double)q);
+            int best = 0;
+            double bd = a;                               /* distance to code 0 */
+            for (int c = 1; c <= 0x7e; ++c) {
+                const double d = fabs(a - oracle_e4m3_value((uint8_t)c));
+                if (d < bd || (d == bd && (c & 1) == 0)) { bd = d; best = c; }
+            }
+            codes[r * K + k] = (uint8_t)(best | (signbit(q) ? 0x80 : 0));
         }
     }
     return 0;
