@@ -36,7 +36,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup(cfg, dev="cuda:0", packed=True):
+def setup(cfg, dev="cuda:0", packed=True, e4m3=False):
     """Profiling -> plan -> evaluation batch -> heaviest rank, all through the library."""
     import torch
     from paper_2603_28768_amd import binding, synth
@@ -66,11 +66,13 @@ def setup(cfg, dev="cuda:0", packed=True):
             dev_w[e] = tuple(binding.to_device(m, cfg.dtype, dev) for m in host_w[e])
     # model loading: weights are re-ordered once for the weight-streaming kernels
     packed = packed and cfg.dtype == "bf16"
-    pk = {e: binding.pack_weights(*dev_w[e]) for e in dev_w} if packed else None
+    pack = binding.pack_weights_e4m3 if e4m3 else binding.pack_weights
+    pk = {e: pack(*dev_w[e]) for e in dev_w} if packed else None
     fwd = binding.RankForward(plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                               [dev_w[e][0] for e in slots], [dev_w[e][1] for e in slots],
                               [dev_w[e][2] for e in slots],
-                              packed=[pk[e] for e in slots] if packed else None)
+                              packed=[pk[e] for e in slots] if packed else None,
+                              weight_format=binding.CRAFT_W_E4M3 if (packed and e4m3) else 0)
     d_x = binding.to_device(x, cfg.dtype, dev)
     # rows per local slot (for the algorithmic byte count): copy q of expert e gets the
     # tokens i < n with i mod c == q
@@ -266,6 +268,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unpacked", action="store_true",
                     help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
+    ap.add_argument("--weights", default="bf16", choices=["bf16", "e4m3"],
+                    help="storage of the packed expert weights: bf16, or E4M3 codes with a scale per row")
     ap.add_argument("--timing-level", type=int, default=1,
                     help="1: HIP events around the gate/up GEMM; 2: around every kernel")
     args = ap.parse_args()
@@ -285,7 +289,10 @@ def main():
     if args.config == "copy_calib":
         return copy_calibration(args)
     cfg = synth.CONFIGS[args.config]
-    st = setup(cfg, packed=not args.unpacked)
+    e4m3 = args.weights == "e4m3"
+    if e4m3:
+        assert cfg.dtype == "bf16" and not args.unpacked, "E4M3 weights go with the packed bf16 path"
+    st = setup(cfg, packed=not args.unpacked, e4m3=e4m3)
     fwd, x, logits = st["fwd"], st["x"], st["logits"]
     M = int(st["rows"][st["rank"]])
     log(f"config {cfg.name}: T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E} k={cfg.k} D={cfg.D}; "
@@ -311,12 +318,13 @@ def main():
     es = 2 if cfg.dtype == "bf16" else 4
     live = sum(1 for r in st["slot_rows"] if r > 0)
     gu_ms = times["gateup"]["ms"] / max(times["gateup"]["launches"], 1)
-    gu_bytes = live * 2 * cfg.H * cfg.I * es + M * cfg.H * es + M * cfg.I * es
+    wes = 1 if e4m3 else es                           # bytes per stored weight
+    gu_bytes = live * 2 * cfg.H * cfg.I * wes + M * cfg.H * es + M * cfg.I * es
     gu_flops = 4.0 * cfg.H * cfg.I * M
     gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
     tfs = gu_flops / (gu_ms * 1e-3) / 1e12
     flop_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
-    traffic = measured_traffic(cfg.name, not args.unpacked and cfg.dtype == "bf16")   # bytes per launch
+    traffic = measured_traffic(cfg.name, not args.unpacked and cfg.dtype == "bf16" and not e4m3)   # bytes per launch
     t_hbm, t_mfma = gu_bytes / (HBM_PEAK_GBS * 1e9), gu_flops / (flop_peak * 1e12)
     if t_hbm >= t_mfma:
         roof = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
@@ -338,7 +346,8 @@ def main():
                                     f"{cfg.replica_slots} replica slots; heaviest rank's share",
                            rank=int(st["rank"]), rank_slots=len(st["slots"]), rank_rows=M,
                            rows_per_s=M / (ms_step * 1e-3), plan_ms=st["plan_ms"],
-                           weights="packed at load" if (not args.unpacked and cfg.dtype == "bf16") else "row-major",
+                           weights=("E4M3 codes + row scales, packed at load" if e4m3 else "packed at load")
+                           if (not args.unpacked and cfg.dtype == "bf16") else "row-major",
                            balancedness_realized=float(np.mean(st["rows"]) / np.max(st["rows"]))),
                roofline=roof)
     if args.timing_level == 2:

@@ -198,6 +198,33 @@ craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void 
                                 const void *w_up, const void *w_down, void *packed_gateup,
                                 void *packed_down, void *stream);
 
+/* ------------------------------------------------------------- 8-bit expert weights
+ * Not in the paper: the bytes of a replica are what its memory budget is spent on, and the
+ * slots with few rows are bound by streaming their weights, so the packed FFN can also run
+ * on weights stored as OCP FP8 E4M3 codes (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits; no infinities; largest finite value 448) with one fp32 scale per weight row.  The
+ * codes are widened to bf16 in registers (exactly) in front of the same bf16 MFMA, and the
+ * scales are applied to the fp32 accumulators.
+ *
+ * craft_quantize_e4m3: scale[r] = max_k |w[r][k]| / 448 in fp32 (1 for an all-zero row);
+ *   codes[r][k] = the E4M3 value nearest to the fp32 quotient w[r][k] / scale[r], ties to the
+ *   even mantissa, the sign bit kept.
+ *     w DEVICE [rows][K] bf16;  codes DEVICE [rows][K] uint8;  scale DEVICE [rows] fp32;  K % 8 == 0
+ * craft_pack_weights_e4m3: the codes of one expert into the streaming order of
+ *   craft_pack_weights (8 bytes per lane instead of 16), the scales appended to the buffers.
+ *     gate/up codes DEVICE [I][H], down codes DEVICE [H][I]; scales [I], [I], [H]
+ *     packed buffers DEVICE, 16-byte aligned, of craft_pack_weights_e4m3_bytes() bytes
+ */
+craft_status craft_quantize_e4m3(const void *w, int64_t rows, int32_t K, uint8_t *codes,
+                                 float *scale, void *stream);
+craft_status craft_pack_weights_e4m3_bytes(int32_t H, int32_t I, size_t *gateup_bytes,
+                                           size_t *down_bytes);
+craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_codes,
+                                     const uint8_t *up_codes, const uint8_t *down_codes,
+                                     const float *gate_scale, const float *up_scale,
+                                     const float *down_scale, void *packed_gateup,
+                                     void *packed_down, void *stream);
+
 /* ------------------------------------------------------------------- execution
  * One rank's share of one MoE layer (Sec. 2.1) under the plan:
  *   1 route       ids, w = top-k of logits                         (as craft_route_topk)
@@ -219,6 +246,8 @@ craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void 
  *                 craft_pack_weights filled for each slot's expert.  When both are given
  *                 (bf16 only) the FFN streams these and w_gate / w_up / w_down may be NULL;
  *                 when NULL the FFN reads the row-major matrices.
+ *   weight_format of the packed buffers: CRAFT_W_BF16 (craft_pack_weights) or CRAFT_W_E4M3
+ *                 (craft_pack_weights_e4m3)
  *   out      DEVICE [T][H] dtype, fully overwritten
  *   ids, topk_w, dest, src  optional DEVICE outputs [T][k] (int32/fp32/int32/int32);
  *                 NULL = kept in the workspace only
@@ -235,6 +264,8 @@ craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void 
  * for bf16 (H % 4, I % 4 for fp32).
  * Limits: T*k < 2^31, k <= 64, E <= 1024, slots of one rank <= 1024.
  */
+enum { CRAFT_W_BF16 = 0, CRAFT_W_E4M3 = 1 };
+
 typedef struct {
     int32_t dtype;
     int64_t T;
@@ -247,6 +278,7 @@ typedef struct {
     const void *const *w_down;
     const void *const *w_gateup_packed;
     const void *const *w_down_packed;
+    int32_t weight_format;
     void *out;
     int32_t *ids;
     float *topk_w;

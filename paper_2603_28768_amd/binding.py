@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcraft.so")
 
 CRAFT_F32, CRAFT_BF16 = 0, 1
+CRAFT_W_BF16, CRAFT_W_E4M3 = 0, 1
 KERNEL_NAMES = ["route", "scan", "dispatch", "gateup", "down", "combine"]
 
 c_i32, c_i64, c_vp, c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
@@ -32,6 +33,7 @@ class FwdArgs(ctypes.Structure):
     _fields_ = [("dtype", c_i32), ("T", c_i64), ("H", c_i32), ("I", c_i32), ("k", c_i32),
                 ("renormalize", c_i32), ("x", c_vp), ("logits", c_vp), ("w_gate", c_vp),
                 ("w_up", c_vp), ("w_down", c_vp), ("w_gateup_packed", c_vp), ("w_down_packed", c_vp),
+                ("weight_format", c_i32),
                 ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
                 ("dest", c_vp), ("src", c_vp), ("counts", c_vp), ("slot_cnt", c_vp),
                 ("slot_off", c_vp), ("max_rows", c_i64), ("tile_rows_gateup", c_i32),
@@ -60,6 +62,10 @@ EXPORTS = {
     "craft_plan_tables_upload": (ctypes.c_int, [c_vp, c_i32, c_i32, c_vp, c_sz, c_vp]),
     "craft_pack_weights_bytes": (ctypes.c_int, [c_i32, c_i32, c_i32, P(c_sz), P(c_sz)]),
     "craft_pack_weights": (ctypes.c_int, [c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp]),
+    "craft_quantize_e4m3": (ctypes.c_int, [c_vp, c_i64, c_i32, c_vp, c_vp, c_vp]),
+    "craft_pack_weights_e4m3_bytes": (ctypes.c_int, [c_i32, c_i32, P(c_sz), P(c_sz)]),
+    "craft_pack_weights_e4m3": (ctypes.c_int, [c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                               c_vp]),
     "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
     "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
     "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32)]),
@@ -272,13 +278,42 @@ def pack_weights(w_gate, w_up, w_down, stream=None):
     return pgu, pdn
 
 
+def quantize_e4m3(w, stream=None):
+    """bf16 device matrix [rows][K] -> (codes uint8 [rows][K], scale fp32 [rows])."""
+    import torch
+    assert w.dtype == torch.bfloat16 and w.dim() == 2 and w.is_contiguous()
+    rows, K = w.shape
+    codes = torch.empty((rows, K), dtype=torch.uint8, device=w.device)
+    scale = torch.empty(rows, dtype=torch.float32, device=w.device)
+    _check(lib().craft_quantize_e4m3(_dev(w), rows, K, _dev(codes), _dev(scale), _stream_ptr(stream)),
+           "craft_quantize_e4m3")
+    return codes, scale
+
+
+def pack_weights_e4m3(w_gate, w_up, w_down, stream=None):
+    """bf16 device matrices of one expert -> E4M3-packed (gateup, down) device buffers."""
+    import torch
+    I, H = w_gate.shape
+    q = [quantize_e4m3(m, stream) for m in (w_gate, w_up, w_down)]
+    a, b = c_sz(), c_sz()
+    _check(lib().craft_pack_weights_e4m3_bytes(H, I, a, b), "craft_pack_weights_e4m3_bytes")
+    pgu = torch.empty(a.value, dtype=torch.uint8, device=w_gate.device)
+    pdn = torch.empty(b.value, dtype=torch.uint8, device=w_gate.device)
+    _check(lib().craft_pack_weights_e4m3(H, I, _dev(q[0][0]), _dev(q[1][0]), _dev(q[2][0]),
+                                         _dev(q[0][1]), _dev(q[1][1]), _dev(q[2][1]),
+                                         _dev(pgu), _dev(pdn), _stream_ptr(stream)),
+           "craft_pack_weights_e4m3")
+    return pgu, pdn
+
+
 class RankForward:
     """Buffers and argument block for repeated forwards of one (plan, layer, rank)."""
 
     def __init__(self, plan: Plan, layer: int, rank: int, dtype: str, T: int, H: int, I: int,
                  k: int, w_gate: Sequence, w_up: Sequence, w_down: Sequence,
                  renormalize: bool = True, max_rows: int = 0, device="cuda:0",
-                 want_debug_outputs: bool = False, packed: Optional[Sequence] = None):
+                 want_debug_outputs: bool = False, packed: Optional[Sequence] = None,
+                 weight_format: int = 0):
         import torch
         self.plan, self.layer, self.rank = plan, layer, rank
         self.dtype, self.T, self.H, self.I, self.k = dtype, T, H, I, k
@@ -318,6 +353,7 @@ class RankForward:
         a.w_gate, a.w_up, a.w_down = (p.data_ptr() for p in self._ptrs)
         if self._packed is not None:
             a.w_gateup_packed, a.w_down_packed = self._packed[1].data_ptr(), self._packed[2].data_ptr()
+            a.weight_format = weight_format
         a.out = self.out.data_ptr()
         for name, t in self.debug.items():
             setattr(a, name, t.data_ptr())

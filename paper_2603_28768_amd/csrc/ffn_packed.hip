@@ -46,6 +46,23 @@ constexpr int kPackGroups = 8;    // the packed stream is padded to whole full-w
 constexpr int XROWB = 64 * 2 + 16;
 constexpr int XSTAGEB = kBM_packed * XROWB;
 
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+// A weight fragment as it sits in the ring: 8 bf16 values, or 8 E4M3 codes that are widened
+// (exactly) right in front of the MFMAs that use them.
+template <bool W8> struct WFrag { typedef bf16x8_t type; };
+template <> struct WFrag<true> { typedef u32x2_t type; };
+template <bool W8> struct WStream { typedef const bf16x8_t __attribute__((address_space(1))) *type; };
+template <> struct WStream<true> { typedef const u32x2_t __attribute__((address_space(1))) *type; };
+
+static __device__ __forceinline__ bf16x8_t widen(bf16x8_t w) { return w; }
+static __device__ __forceinline__ bf16x8_t widen(u32x2_t w) {
+    // two codes per conversion (bytes 0,1 / 2,3 of a word), then pairs of fp32 to bf16
+    const f32x2_t a = __builtin_amdgcn_cvt_pk_f32_fp8(w[0], false), b = __builtin_amdgcn_cvt_pk_f32_fp8(w[0], true);
+    const f32x2_t c = __builtin_amdgcn_cvt_pk_f32_fp8(w[1], false), d = __builtin_amdgcn_cvt_pk_f32_fp8(w[1], true);
+    typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+    const u32x4v r = {bf16_pair(a[0], a[1]), bf16_pair(b[0], b[1]), bf16_pair(c[0], c[1]), bf16_pair(d[0], d[1])};
+    return __builtin_bit_cast(bf16x8_t, r);
+}
 typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global address space
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
@@ -61,9 +78,9 @@ typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 //                         the same registers are requested again for the slab after it behind
 //                         the next MFMA
 //   a group's last MFMA : + refill of the weight ring slot that group has just used
-template <int NXF, int NGT, int R, int PW, int PHASE>
-__device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, wstream_t wp,
-                                            int64_t wstride, bf16x8_t (&wq)[NGT][PW],
+template <int NXF, int NGT, int R, int PW, int PHASE, bool W8>
+__device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, typename WStream<W8>::type wp,
+                                            int64_t wstride, typename WFrag<W8>::type (&wq)[NGT][PW],
                                             const bf16x8_t (&XC)[NXF], bf16x8_t (&XN)[NXF],
                                             f32x16_t (&acc)[NGT][NXF], unsigned char *xstage,
                                             u32x4_t (&XR)[NXF], const unsigned short *const (&xp)[NXF],
@@ -71,10 +88,11 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
     constexpr int HALF = (NXF + 1) / 2;
     const int64_t nxt = min(step + PW, ksteps - 1) * wstride;
 #pragma unroll
-    for (int n = 0; n < NGT; ++n)
+    for (int n = 0; n < NGT; ++n) {
+        const bf16x8_t wf = widen(wq[n][R]);
 #pragma unroll
         for (int g = 0; g < NXF; ++g) {
-            acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq[n][R], XC[g], acc[n][g], 0, 0, 0);
+            acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, XC[g], acc[n][g], 0, 0, 0);
             if (n == 0) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
             if (n == NGT - 1 && PHASE < 2) {
                 // chunk i: its LDS write behind an even MFMA, its new request behind the next one
@@ -87,6 +105,7 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
             if (g == NXF - 1) wq[n][R] = wp[nxt + n * 64];
             __builtin_amdgcn_sched_barrier(0);
         }
+    }
 }
 
 // One 64-wide slab U (0..3) of a group of four.  On entry LDS stage `cur` holds this slab,
@@ -95,26 +114,26 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
 // ahead is requested from global memory into the same registers; the last step already
 // fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
 // enough: a stage is rewritten a full slab after its last reader has passed a barrier.
-template <int NXF, int NGT, int U, int PW>
+template <int NXF, int NGT, int U, int PW, bool W8>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
-                                            wstream_t wp, int64_t wstride,
-                                            const unsigned short *const (&xp)[NXF], bf16x8_t (&wq)[NGT][PW],
+                                            typename WStream<W8>::type wp, int64_t wstride,
+                                            const unsigned short *const (&xp)[NXF], typename WFrag<W8>::type (&wq)[NGT][PW],
                                             u32x4_t (&XR)[NXF], bf16x8_t (&X0)[NXF], bf16x8_t (&X1)[NXF],
                                             f32x16_t (&acc)[NGT][NXF]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
     const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, NGT, (U * 4 + 0) % PW, PW, 0>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 1) % PW, PW, 1>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 0) % PW, PW, 0, W8>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 1) % PW, PW, 1, W8>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
     __syncthreads();
-    packed_step<NXF, NGT, (U * 4 + 2) % PW, PW, 2>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 3) % PW, PW, 2>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 2) % PW, PW, 2, W8>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 3) % PW, PW, 2, W8>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
 }
 
 // One tile with NXF live 32-row activation fragments.
-template <bool GATEUP, int NXF, int NGT>
+template <bool GATEUP, int NXF, int NGT, bool W8>
 __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, unsigned char *smem,
                                             int K, int N, int ngroups, int nk4, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
@@ -129,7 +148,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
     // of a tile has a stream to read even past the last real column.
     const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
-    wstream_t wp = (wstream_t)wbase + (int64_t)group0 * 64 + lane;
+    typename WStream<W8>::type wp = (typename WStream<W8>::type)wbase + (int64_t)group0 * 64 + lane;
     const int64_t wstride = (int64_t)groups_padded * 64;
     const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
 
@@ -153,7 +172,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     // Request order: half the weight ring, the first two activation slabs, the other half of
     // the ring.  The second slab is then followed by as many weight requests as in the loop,
     // so the in-order load counter need not be drained when the loop is entered.
-    bf16x8_t wq[NGT][PW];
+    typename WFrag<W8>::type wq[NGT][PW];
     u32x4_t xr[NXF];
     {
         u32x4_t xfirst[NXF];
@@ -188,10 +207,10 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
         unsigned char *s0 = smem + st * XSTAGEB;
         unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
         unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
-        packed_slab<NXF, NGT, 0, PW>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 1, PW>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 2, PW>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 3, PW>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 0, PW, W8>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 1, PW, W8>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 2, PW, W8>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
+        packed_slab<NXF, NGT, 3, PW, W8>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
         st = (st + 1) % 3;
     }
 
@@ -204,24 +223,48 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     // 16-byte stores, half as many as 8-byte ones would be.
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
+    // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows, then
+    // up rows; or down rows) and multiplies the accumulator of that output column
+    const float *wscale = reinterpret_cast<const float *>(
+        static_cast<const unsigned char *>(wbase) + (size_t)groups_padded * ksteps * 512);
 #pragma unroll
     for (int n = 0; n < NGT; ++n) {
         const int cbase = (group0 + n) * GC;
+        constexpr int NVG = GATEUP ? 2 : 4;        // blocks of 8 output columns per group
+        // the scales depend on the column only: fetched once per group, not once per fragment
+        float sa[NVG][4], sb[NVG][4];
+#pragma unroll
+        for (int vg = 0; vg < NVG; ++vg)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sa[vg][c] = sb[vg][c] = 1.0f;
+        if (W8) {
+#pragma unroll
+            for (int vg = 0; vg < NVG; ++vg) {
+                const int c0 = min(cbase + vg * 8 + (lane >> 5) * 4, N - 4);   // padding columns: any valid scale
+                const float4 va = *reinterpret_cast<const float4 *>(wscale + c0);
+                sa[vg][0] = va.x; sa[vg][1] = va.y; sa[vg][2] = va.z; sa[vg][3] = va.w;
+                if (GATEUP) {
+                    const float4 vb = *reinterpret_cast<const float4 *>(wscale + N + c0);
+                    sb[vg][0] = vb.x; sb[vg][1] = vb.y; sb[vg][2] = vb.z; sb[vg][3] = vb.w;
+                }
+            }
+        }
 #pragma unroll
         for (int g = 0; g < NXF; ++g) {
             const int m = g * 32 + (lane & 31);
             unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
             // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
 #pragma unroll
-            for (int vg = 0; vg < (GATEUP ? 2 : 4); vg += 2) {
+            for (int vg = 0; vg < NVG; vg += 2) {
                 uint32_t piece[2][2];
 #pragma unroll
                 for (int b = 0; b < 2; ++b) {
                     float h[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c]) * acc[n][g][8 + (vg + b) * 4 + c]
-                                      : acc[n][g][(vg + b) * 4 + c];
+                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c] * sa[vg + b][c]) *
+                                            (acc[n][g][8 + (vg + b) * 4 + c] * sb[vg + b][c])
+                                      : acc[n][g][(vg + b) * 4 + c] * sa[vg + b][c];
                     piece[b][0] = bf16_pair(h[0], h[1]);
                     piece[b][1] = bf16_pair(h[2], h[3]);
                 }
@@ -238,7 +281,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     }
 }
 
-template <bool GATEUP>
+template <bool GATEUP, bool W8>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
     __shared__ int64_t next_item;
@@ -267,14 +310,14 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
         if (w < hot_tiles) {
             const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
             switch ((t.rows + 31) >> 5) {          // live 32-row fragments of this tile
-                case 1: packed_tile<GATEUP, 1, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 2: packed_tile<GATEUP, 2, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 3: packed_tile<GATEUP, 3, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 4: packed_tile<GATEUP, 4, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 5: packed_tile<GATEUP, 5, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 6: packed_tile<GATEUP, 6, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 7: packed_tile<GATEUP, 7, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                default: packed_tile<GATEUP, 8, NG>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 1: packed_tile<GATEUP, 1, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 2: packed_tile<GATEUP, 2, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 3: packed_tile<GATEUP, 3, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 4: packed_tile<GATEUP, 4, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 5: packed_tile<GATEUP, 5, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 6: packed_tile<GATEUP, 6, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                case 7: packed_tile<GATEUP, 7, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                default: packed_tile<GATEUP, 8, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
             }
         } else {
             const int64_t cw = w - hot_tiles;
@@ -286,8 +329,8 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
             t.m0 = 0;
             t.n0 = (int32_t)(cw % (2 * nt)) * (BN / 2);
             if (t.n0 < N) {                        // the last half may lie past the matrix
-                if (t.rows <= 32) packed_tile<GATEUP, 1, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos);
-                else packed_tile<GATEUP, 2, 1>(a, t, smem, K, N, ngroups, nk4, lo_pos);
+                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos);
+                else packed_tile<GATEUP, 2, 1, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos);
             }
         }
         if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
@@ -332,7 +375,8 @@ hipError_t launch_packed(const FfnArgs &a, hipStream_t s) {
     const int64_t bound = (a.max_rows / (32 * std::abs(GATEUP ? a.frags_gu : a.frags_dn)) + 2 * a.nslots) * nt;
     int64_t grid = std::min<int64_t>(bound, (int64_t)a.num_cu);
     grid = std::max<int64_t>(8, (grid + 7) / 8 * 8);
-    hipLaunchKernelGGL(ffn_packed_kernel<GATEUP>, dim3((unsigned)grid), dim3(256), 0, s, a);
+    if (a.w8) hipLaunchKernelGGL((ffn_packed_kernel<GATEUP, true>), dim3((unsigned)grid), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((ffn_packed_kernel<GATEUP, false>), dim3((unsigned)grid), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -280,6 +280,40 @@ craft_status craft_pack_weights(int32_t dtype, int32_t H, int32_t I, const void 
                    hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
 
+craft_status craft_quantize_e4m3(const void *w, int64_t rows, int32_t K, uint8_t *codes, float *scale,
+                                 void *stream) {
+    if (rows < 0 || K <= 0 || K % 8) return CRAFT_EINVAL;
+    if (rows == 0) return CRAFT_OK;
+    if (!w || !codes || !scale || !aligned(w, 16) || !aligned(codes, 8) || !aligned(scale, 4))
+        return CRAFT_EINVAL;
+    return launch_quantize_e4m3(w, rows, K, codes, scale, as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                             : CRAFT_EHIP;
+}
+
+craft_status craft_pack_weights_e4m3_bytes(int32_t H, int32_t I, size_t *gateup_bytes,
+                                           size_t *down_bytes) {
+    if (H <= 0 || I <= 0 || H % 8 || I % 8 || !gateup_bytes || !down_bytes) return CRAFT_EINVAL;
+    packed_sizes_e4m3(H, I, gateup_bytes, down_bytes);
+    return CRAFT_OK;
+}
+
+craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_codes,
+                                     const uint8_t *up_codes, const uint8_t *down_codes,
+                                     const float *gate_scale, const float *up_scale,
+                                     const float *down_scale, void *packed_gateup,
+                                     void *packed_down, void *stream) {
+    if (H <= 0 || I <= 0 || H % 8 || I % 8) return CRAFT_EINVAL;
+    if (!gate_codes || !up_codes || !down_codes || !gate_scale || !up_scale || !down_scale ||
+        !packed_gateup || !packed_down)
+        return CRAFT_EINVAL;
+    if (!aligned(gate_codes, 8) || !aligned(up_codes, 8) || !aligned(down_codes, 8) ||
+        !aligned(packed_gateup, 16) || !aligned(packed_down, 16))
+        return CRAFT_EINVAL;
+    return launch_pack_e4m3(H, I, gate_codes, up_codes, down_codes, gate_scale, up_scale, down_scale,
+                            packed_gateup, packed_down, as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                          : CRAFT_EHIP;
+}
+
 craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                               const craft_fwd_args *a, size_t *bytes) {
     if (!bytes) return CRAFT_EINVAL;
@@ -318,6 +352,8 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
         const bool packed = a->w_gateup_packed && a->w_down_packed;
         if ((a->w_gateup_packed != nullptr) != (a->w_down_packed != nullptr)) return CRAFT_EINVAL;
         if (packed && a->dtype != CRAFT_BF16) return CRAFT_EINVAL;
+        if (a->weight_format != CRAFT_W_BF16 && a->weight_format != CRAFT_W_E4M3) return CRAFT_EINVAL;
+        if (a->weight_format == CRAFT_W_E4M3 && !packed) return CRAFT_EINVAL;
         if (nslots > 0 && !packed && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
     }
     hipStream_t s = as_stream(stream);
@@ -364,7 +400,8 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 4 grouped FFN
     FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, order, ctrl,
                a->w_gate, a->w_up, a->w_down, a->w_gateup_packed, a->w_down_packed,
-               ws + L.act, ws + L.y, L.max_rows, cached_num_cu(), frags.first, frags.second};
+               ws + L.act, ws + L.y, L.max_rows, cached_num_cu(), a->weight_format == CRAFT_W_E4M3 ? 1 : 0,
+               frags.first, frags.second};
     if (a->T > 0) {
         {
             ScopedEvent ev(CRAFT_K_GATEUP, s);

@@ -93,6 +93,7 @@ struct FfnArgs {
     void *y;                       // [max_rows][H]
     int64_t max_rows;
     int32_t num_cu;
+    int32_t w8;                    // packed weights are E4M3 codes with row scales behind the stream
     int32_t frags_gu, frags_dn;    // most 32-row fragments per row-tile the tile tables were built for;
                                    // negative: fragments shared evenly among a slot's row-tiles
 };
@@ -103,6 +104,12 @@ hipError_t launch_down_packed(const FfnArgs &a, hipStream_t s);
 void packed_sizes(int32_t H, int32_t I, size_t *gateup_bytes, size_t *down_bytes);
 hipError_t launch_pack(int32_t H, int32_t I, const void *wg, const void *wu, const void *wd,
                        void *pgu, void *pdn, hipStream_t s);
+void packed_sizes_e4m3(int32_t H, int32_t I, size_t *gateup_bytes, size_t *down_bytes);
+hipError_t launch_quantize_e4m3(const void *w, int64_t rows, int32_t K, uint8_t *codes, float *scale,
+                                hipStream_t s);
+hipError_t launch_pack_e4m3(int32_t H, int32_t I, const uint8_t *cg, const uint8_t *cu, const uint8_t *cd,
+                            const float *sg, const float *su, const float *sd, void *pgu, void *pdn,
+                            hipStream_t s);
 
 struct CombineArgs {
     int32_t dtype;

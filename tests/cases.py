@@ -11,11 +11,12 @@ from paper_2603_28768_amd import binding, synth
 
 
 class Case:
-    def __init__(self, cfg: synth.LayerConfig, plan=None, layer: int = 0, pop=None):
+    def __init__(self, cfg: synth.LayerConfig, plan=None, layer: int = 0, pop=None, w8: bool = False):
         """Without `plan`: a one-layer plan is made from this config's profiling batches.
         With `plan` (and the layer's popularity `pop`): the evaluation batch of layer
         `layer` of a multi-layer plan made elsewhere."""
         self.cfg = cfg
+        self.w8 = w8                      # expert weights stored as E4M3 codes with row scales
         self.layer_index = layer
         self.pop = synth.layer_popularity(cfg, layer) if pop is None else pop
         if plan is None:
@@ -43,8 +44,13 @@ class Case:
         self._wcache = {}
 
     def weights_of(self, e: int):
+        """What the checker multiplies with: the synthetic weights, or with w8 what their 8-bit
+        storage decodes to (quantised by the checker itself)."""
         if e not in self._wcache:
-            self._wcache[e] = synth.expert_weights(self.cfg, e, self.layer_index)
+            w = synth.expert_weights(self.cfg, e, self.layer_index)
+            if self.w8:
+                w = tuple(oracle.dequantize_e4m3(*oracle.quantize_e4m3(m)) for m in w)
+            self._wcache[e] = w
         return self._wcache[e]
 
     def rank_slots(self, rank: int):
@@ -64,16 +70,18 @@ class Case:
         dev_cache, pack_cache = {}, {}
         for e in self.rank_slots(rank):
             if e not in dev_cache:
-                dev_cache[e] = tuple(binding.to_device(m, cfg.dtype, device) for m in self.weights_of(e))
+                raw = synth.expert_weights(cfg, e, self.layer_index)       # the library quantises itself
+                dev_cache[e] = tuple(binding.to_device(m, cfg.dtype, device) for m in raw)
                 if packed:
-                    pack_cache[e] = binding.pack_weights(*dev_cache[e])
+                    pack_cache[e] = (binding.pack_weights_e4m3 if self.w8 else binding.pack_weights)(*dev_cache[e])
             g, u, d = dev_cache[e]
             wg.append(g); wu.append(u); wd.append(d)
             if packed:
                 pk.append(pack_cache[e])
         fwd = binding.RankForward(self.plan, self.layer_index, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                                   wg, wu, wd, True, max_rows, device, want_debug_outputs=debug,
-                                  packed=pk if packed else None)
+                                  packed=pk if packed else None,
+                                  weight_format=binding.CRAFT_W_E4M3 if (packed and self.w8) else 0)
         x = binding.to_device(self.x, cfg.dtype, device)
         logits = torch.from_numpy(self.logits).to(device)
         return fwd, x, logits

@@ -276,3 +276,37 @@ def test_full_size_heaviest_rank_sampled(torch_cuda, name):
     toks = _sampled_tokens(case, g, 12)
     _check_rank(torch_cuda, case, g, tokens=toks, packed=True)
     _check_rank(torch_cuda, case, g, tokens=toks, packed=False)
+
+
+# ------------------------------------------------------------- 8-bit expert weights
+
+@pytest.mark.parametrize("rows,K,scale", [(7, 64, 1.0), (33, 520, 0.02), (5, 4096, 30.0), (1, 8, 1.0)])
+def test_quantize_e4m3_parity(torch_cuda, rows, K, scale):
+    torch = torch_cuda
+    g = np.random.default_rng(rows * 1000 + K)
+    W = synth.round_to_storage((g.standard_normal((rows, K)) * scale).astype(np.float32), "bf16")
+    W[0, :8] = [0.0, -0.0, 1.0625, 1.1875, -1.0625, 448.0, 2.0 ** -10, 3 * 2.0 ** -10]   # zeros, ties, top
+    if rows > 2:
+        W[2] = 0.0                                                    # an all-zero row: scale 1
+    codes, sc = binding.quantize_e4m3(binding.to_device(W, "bf16", "cuda:0"))
+    want_c, want_s = oracle.quantize_e4m3(W)
+    assert np.array_equal(sc.cpu().numpy(), want_s)
+    assert np.array_equal(codes.cpu().numpy(), want_c)
+
+
+@pytest.mark.parametrize("T,H,I,E,k,D,slots", [
+    (600, 512, 384, 32, 4, 4, 4),          # several row tiles, ragged last tile
+    (517, 520, 200, 24, 8, 3, 5),          # ragged K and N
+    (40, 128, 64, 6, 1, 2, 2)])            # top-1, cold slots only
+def test_reduced_layers_with_e4m3_weights(torch_cuda, T, H, I, E, k, D, slots):
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=T, H=H, I=I, E=E, k=k, D=D, replica_slots=slots,
+                       zipf_s=1.2, profile_batches=2)
+    case = Case(cfg, w8=True)
+    for g in range(D):
+        _check_rank(torch_cuda, case, g, packed=True)
+
+
+def test_full_size_qwen3_with_e4m3_weights(torch_cuda):
+    case = Case(synth.CONFIGS["qwen3"], w8=True)
+    g = case.heaviest
+    _check_rank(torch_cuda, case, g, tokens=_sampled_tokens(case, g, 12), packed=True)
