@@ -256,8 +256,9 @@ craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_c
  *   max_rows rows the staging buffers are sized for.  0 = the worst case
  *            T * min(k, s).  If the batch routes more rows than this to the rank the
  *            forward does no FFN work, zero-fills out and sets the overflow flag.
- *   tile_rows_gateup, tile_rows_down  tuning knobs of the packed FFN, normally 0: see
- *            craft_moe_rank_forward_tiles for what the library picks by itself
+ *   tile_rows_gateup, tile_rows_down, riders_gateup, riders_down  tuning knobs of the packed
+ *            FFN, normally 0: see craft_moe_rank_forward_tiles for what the library picks by
+ *            itself
  *   workspace DEVICE, 256-byte aligned, at least craft_moe_rank_forward_workspace() bytes.
  *            Forwards that share a workspace must be ordered on one stream.
  * Alignment: x, out and all weight matrices 16-byte aligned; H % 8 == 0 and I % 8 == 0
@@ -290,6 +291,9 @@ typedef struct {
     int64_t max_rows;
     int32_t tile_rows_gateup;  /* packed weights only: rows per row-tile of the gate/up GEMM, */
     int32_t tile_rows_down;    /* of the down GEMM: 128, 160, .., 256; 0 = chosen by the library */
+    int32_t riders_gateup;     /* packed weights only: slots with at most 64 rows ride along with the */
+    int32_t riders_down;       /* tiles of busy slots: 1 = wherever tiles are at most 224 rows, -1 = never,
+                                  0 = chosen by the library */
     const void *tables;        /* from craft_plan_tables_upload */
     void *workspace;
     size_t workspace_bytes;
@@ -301,13 +305,17 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
 craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                     const craft_fwd_args *args, void *stream);
 
-/* The most rows a row-tile of the two grouped GEMMs gets in forwards with these arguments
- * (a multiple of 32).  With packed weights it is chosen per (plan, layer, rank, T, k, H, I)
- * from the loads the plan was made from, so that the tiles of the busy slots fill the CUs
- * in whole rounds; the choice is kept in the plan.  Host-side, no device work. */
+/* How forwards with these arguments cut the two grouped GEMMs into tiles: the most rows a
+ * row-tile gets (a multiple of 32), and whether the slots with few rows are carried along by
+ * the tiles of the busy slots (1) or get tiles of their own (0).  With packed weights both
+ * are chosen per (plan, layer, rank, T, k, H, I) from the loads the plan was made from, by
+ * playing the launch through against a cost model, so that the tiles of the busy slots fill
+ * the CUs in whole rounds; the choice is kept in the plan.  Any output pointer may be NULL.
+ * Host-side, no device work. */
 craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                           const craft_fwd_args *args, int32_t *rows_gateup,
-                                          int32_t *rows_down);
+                                          int32_t *rows_down, int32_t *riders_gateup,
+                                          int32_t *riders_down);
 
 /* After the caller has synchronised the stream: what the last forward on this workspace
  * found.  rows = rows routed to the rank; overflow != 0 when rows > max_rows (nothing was

@@ -37,7 +37,8 @@ class FwdArgs(ctypes.Structure):
                 ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
                 ("dest", c_vp), ("src", c_vp), ("counts", c_vp), ("slot_cnt", c_vp),
                 ("slot_off", c_vp), ("max_rows", c_i64), ("tile_rows_gateup", c_i32),
-                ("tile_rows_down", c_i32), ("tables", c_vp), ("workspace", c_vp),
+                ("tile_rows_down", c_i32), ("riders_gateup", c_i32), ("riders_down", c_i32),
+                ("tables", c_vp), ("workspace", c_vp),
                 ("workspace_bytes", c_sz)]
 
 
@@ -68,7 +69,8 @@ EXPORTS = {
                                                c_vp]),
     "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
     "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
-    "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32)]),
+    "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32),
+                                                    P(c_i32), P(c_i32)]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
     "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
     "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
@@ -380,13 +382,18 @@ class RankForward:
                "craft_moe_rank_forward")
         return self.out
 
+    def tile_choice(self):
+        """Row-tile heights and rider switches the forward uses: (rows gate/up, rows down,
+        riders gate/up, riders down)."""
+        g, d, rg, rd = c_i32(), c_i32(), c_i32(), c_i32()
+        _check(lib().craft_moe_rank_forward_tiles(self.plan._h, self.layer, self.rank,
+                                                  ctypes.byref(self.args), g, d, rg, rd),
+               "craft_moe_rank_forward_tiles")
+        return g.value, d.value, rg.value, rd.value
+
     def tile_rows(self):
         """(gate/up, down) row-tile heights the forward uses."""
-        g, d = c_i32(), c_i32()
-        _check(lib().craft_moe_rank_forward_tiles(self.plan._h, self.layer, self.rank,
-                                                  ctypes.byref(self.args), g, d),
-               "craft_moe_rank_forward_tiles")
-        return g.value, d.value
+        return self.tile_choice()[:2]
 
     def result(self):
         """(rows routed to the rank, overflow flag) of the last forward; synchronises."""

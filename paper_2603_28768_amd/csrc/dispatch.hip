@@ -183,37 +183,53 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         sorted_rows[pos] = mine;
     }
     __syncthreads();
-    // row-tiles per slot: its 32-row fragments over the launch's tile height, rounded up
-    int32_t mtotal[2];
-    for (int kind = 0; kind < 2; ++kind) {
-        const int32_t fmax = abs(kind == 0 ? a.frags_gu : a.frags_dn);
-        int32_t *mt_out = a.mt_start + kind * (nslots + 1);
-        int32_t mcarry = 0;
-        for (int32_t base = 0; base < nslots; base += kScanThreads) {
-            const int32_t pos = base + threadIdx.x;
-            int32_t mt = 0;
-            if (pos < nslots && !ovf) mt = (((sorted_rows[pos] + 31) >> 5) + fmax - 1) / fmax;
-            int32_t chunk_total;
-            const int32_t off = mcarry + block_exclusive_scan(mt, wsum, &chunk_total);
-            if (pos < nslots) mt_out[pos] = off;
-            mcarry += chunk_total;
-        }
-        if (threadIdx.x == 0) mt_out[nslots] = mcarry;
-        mtotal[kind] = mcarry;
-    }
-    // the busy and the live slots are prefixes of the busiest-first order
-    __shared__ int32_t prefix_len[2];
-    if (threadIdx.x == 0) prefix_len[0] = prefix_len[1] = 0;
+    // the busy and the live slots are prefixes of the busiest-first order, and so are the slots
+    // with more than one fragment
+    __shared__ int32_t prefix_len[3];
+    if (threadIdx.x < 3) prefix_len[threadIdx.x] = 0;
     __syncthreads();
     for (int32_t pos = threadIdx.x; pos < nslots; pos += kScanThreads) {
         const int32_t r = sorted_rows[pos], nxt = pos + 1 < nslots ? sorted_rows[pos + 1] : 0;
         if (r > kColdRows && nxt <= kColdRows) prefix_len[0] = pos + 1;
         if (r > 0 && nxt <= 0) prefix_len[1] = pos + 1;
+        if (r > 32 && nxt <= 32) prefix_len[2] = pos + 1;
     }
     __syncthreads();
+    const int32_t hot = ovf ? 0 : prefix_len[0], live = ovf ? 0 : prefix_len[1];
+    const int32_t ncold = live - hot;
+    const int32_t ncold2 = max(0, min(prefix_len[2], live) - hot);   // cold slots with two fragments
+    // row-tiles per slot: its 32-row fragments over the launch's tile height, rounded up
+    int32_t mtotal[2], riders[2];
+    __shared__ int32_t hot_mtiles;
+    for (int kind = 0; kind < 2; ++kind) {
+        const int32_t fmax = abs(kind == 0 ? a.frags_gu : a.frags_dn);
+        int32_t *mt_out = a.mt_start + kind * (nslots + 1);
+        const int32_t pos = threadIdx.x;           // at most kScanThreads slots per rank
+        const int32_t F = pos < nslots && !ovf ? (sorted_rows[pos] + 31) >> 5 : 0;
+        const int32_t mt = (F + fmax - 1) / fmax;
+        int32_t mcarry;
+        const int32_t off = block_exclusive_scan(mt, wsum, &mcarry);
+        if (pos < nslots) mt_out[pos] = off;
+        if (pos == hot) hot_mtiles = off;          // row-tiles of the busy slots
+        if (threadIdx.x == 0 && hot >= kScanThreads) hot_mtiles = mcarry;
+        if (threadIdx.x == 0) mt_out[nslots] = mcarry;
+        mtotal[kind] = mcarry;
+        __syncthreads();
+        // rider units: one per tile of the busy slots while they last; a two-fragment slot
+        // (4 nt units) is carried whole or not at all
+        const int64_t nt = kind == 0 ? a.nt_gu : a.nt_dn;
+        const int64_t units2 = (int64_t)ncold2 * 4 * nt, units = units2 + (int64_t)(ncold - ncold2) * 2 * nt;
+        int64_t carried = fmax <= kRiderHostFrags ? min((int64_t)hot_mtiles * nt, units) : 0;
+        if (carried < units2) carried = carried / (4 * nt) * (4 * nt);
+        riders[kind] = (int32_t)carried;
+        __syncthreads();                           // hot_mtiles is rewritten by the next kind
+    }
     if (threadIdx.x == 0) {
-        a.ctrl[CTRL_HOT_SLOTS] = ovf ? 0 : prefix_len[0];
-        a.ctrl[CTRL_LIVE_SLOTS] = ovf ? 0 : prefix_len[1];
+        a.ctrl[CTRL_HOT_SLOTS] = hot;
+        a.ctrl[CTRL_LIVE_SLOTS] = live;
+        a.ctrl[CTRL_COLD2_SLOTS] = ncold2;
+        a.ctrl[CTRL_RIDERS_GATEUP] = riders[0];
+        a.ctrl[CTRL_RIDERS_DOWN] = riders[1];
         a.ctrl[CTRL_ROWS] = rank_rows;
         a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
         a.ctrl[CTRL_MTILES] = mtotal[0];

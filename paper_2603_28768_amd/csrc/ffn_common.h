@@ -16,6 +16,7 @@ struct Tile {
     int32_t rows;      // valid rows in this tile
     int32_t n0;        // first output column
     int32_t pos0;      // global dispatch position of the slot's first row
+    int32_t mtile;     // index of the row-tile in the list of all row-tiles of the busy slots
 };
 
 // Flattened work item w -> tile.  nt = column tiles per slot, bn = columns per tile.
@@ -65,6 +66,7 @@ static __device__ __forceinline__ Tile decode_tile_in(int32_t nslots, const MT &
     t.m0 = f0 * 32;
     t.rows = min(f1 * 32, slot_rows) - t.m0;
     t.n0 = (rem / mts) * bn;
+    t.mtile = mt_first + i;
     return t;
 }
 static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, const int32_t *mt_start, int64_t w,

@@ -40,7 +40,10 @@ namespace {
 // Weight steps kept in flight per column group: deep for the streaming-bound tiles with few
 // row fragments, shallower where the accumulators need the registers and each step carries
 // enough MFMA work to cover the latency.
-constexpr int ring_depth(int nxf) { return nxf >= 3 ? 8 : 16; }
+constexpr int ring_depth(int nxa) { return nxa >= 3 ? 8 : 16; }
+// The rider's weights always come from HBM (nobody else reads them): where the registers are
+// there its ring runs twice as far ahead as the tile's own.
+constexpr int rider_ring(int nxf, bool w8) { return w8 || nxf <= 4 ? 16 : 8; }
 constexpr int NG = 2;             // column groups per wave in a full-width tile (1 in a half-width one)
 constexpr int kPackGroups = 8;    // the packed stream is padded to whole full-width tiles
 constexpr int XROWB = 64 * 2 + 16;
@@ -63,8 +66,16 @@ static __device__ __forceinline__ bf16x8_t widen(u32x2_t w) {
     const u32x4v r = {bf16_pair(a[0], a[1]), bf16_pair(b[0], b[1]), bf16_pair(c[0], c[1]), bf16_pair(d[0], d[1])};
     return __builtin_bit_cast(bf16x8_t, r);
 }
-typedef const bf16x8_t __attribute__((address_space(1))) *wstream_t;   // global address space
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));      // native vector: stays in VGPRs
+template <bool W8> static __device__ __forceinline__ typename WFrag<W8>::type zero_fragment();
+template <> __device__ __forceinline__ bf16x8_t zero_fragment<false>() {
+    const u32x4_t z = {0u, 0u, 0u, 0u};
+    return __builtin_bit_cast(bf16x8_t, z);
+}
+template <> __device__ __forceinline__ u32x2_t zero_fragment<true>() {
+    const u32x2_t z = {0u, 0u};
+    return z;
+}
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 
 // One 16-wide contraction step of NGT x NXF MFMAs (NGT column groups per wave).  A wave is alone on its SIMD, so whatever
@@ -78,31 +89,45 @@ typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 //                         the same registers are requested again for the slab after it behind
 //                         the next MFMA
 //   a group's last MFMA : + refill of the weight ring slot that group has just used
-template <int NXF, int NGT, int R, int PW, int PHASE, bool W8>
+//   the rider, if any   : fragment NXF of the activations belongs to a cold slot and meets one
+//                         column group of that slot's weights (a ring of its own): one more
+//                         MFMA at the end of the last group's, its LDS read behind that
+//                         group's first MFMA, its refill behind itself
+template <int NXF, int NGT, int R, int RR, int PW, int PHASE, bool W8, bool RIDER>
 __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, typename WStream<W8>::type wp,
-                                            int64_t wstride, typename WFrag<W8>::type (&wq)[NGT][PW],
-                                            const bf16x8_t (&XC)[NXF], bf16x8_t (&XN)[NXF],
-                                            f32x16_t (&acc)[NGT][NXF], unsigned char *xstage,
-                                            u32x4_t (&XR)[NXF], const unsigned short *const (&xp)[NXF],
+                                            typename WStream<W8>::type wpr, int64_t wstride,
+                                            typename WFrag<W8>::type (&wq)[NGT][PW],
+                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
+                                            const bf16x8_t (&XC)[NXF + RIDER], bf16x8_t (&XN)[NXF + RIDER],
+                                            f32x16_t (&acc)[NGT][NXF], f32x16_t (&accr)[1][1], unsigned char *xstage,
+                                            u32x4_t (&XR)[NXF + RIDER], xchunk_t xin, const uint32_t (&xp)[NXF + RIDER],
                                             int koff) {
-    constexpr int HALF = (NXF + 1) / 2;
+    static_assert(!RIDER || NGT >= 2, "a rider needs a group of its own to hide behind");
+    constexpr int NXA = NXF + (RIDER ? 1 : 0);     // activation fragments in LDS, the rider's last
+    constexpr int HALF = (NXA + 1) / 2;
     const int64_t nxt = min(step + PW, ksteps - 1) * wstride;
 #pragma unroll
     for (int n = 0; n < NGT; ++n) {
+        const bool last = n == NGT - 1;
         const bf16x8_t wf = widen(wq[n][R]);
 #pragma unroll
-        for (int g = 0; g < NXF; ++g) {
-            acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, XC[g], acc[n][g], 0, 0, 0);
-            if (n == 0) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
-            if (n == NGT - 1 && PHASE < 2) {
+        for (int g = 0; g < NXA; ++g) {
+            if (g < NXF) acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, XC[g], acc[n][g], 0, 0, 0);
+            else if (last) accr[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen(wr[RIDER ? RR % rider_ring(NXF, W8) : 0]), XC[g], accr[0][0], 0, 0, 0);
+            else continue;
+            if (n == 0 && g < NXF) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
+            if (RIDER && last && g == 0) XN[NXF] = *reinterpret_cast<const bf16x8_t *>(xnext + NXF * 32 * XROWB);
+            if (last && PHASE < 2) {
                 // chunk i: its LDS write behind an even MFMA, its new request behind the next one
                 const int i = PHASE * HALF + g / 2;
-                if (i < NXF && i < (PHASE + 1) * HALF) {
+                if (i < NXA && i < (PHASE + 1) * HALF) {
                     if ((g & 1) == 0) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
-                    if ((g & 1) == 1 || g == NXF - 1) XR[i] = *(xchunk_t)(xp[i] + koff);
+                    if ((g & 1) == 1 || g == NXA - 1) XR[i] = xin[(size_t)xp[i] + koff];
                 }
             }
             if (g == NXF - 1) wq[n][R] = wp[nxt + n * 64];
+            if (RIDER && last && g == NXA - 1)
+                wr[RR % rider_ring(NXF, W8)] = wpr[min(step + rider_ring(NXF, W8), ksteps - 1) * wstride];
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -114,124 +139,50 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
 // ahead is requested from global memory into the same registers; the last step already
 // fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
 // enough: a stage is rewritten a full slab after its last reader has passed a barrier.
-template <int NXF, int NGT, int U, int PW, bool W8>
+template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
-                                            typename WStream<W8>::type wp, int64_t wstride,
-                                            const unsigned short *const (&xp)[NXF], typename WFrag<W8>::type (&wq)[NGT][PW],
-                                            u32x4_t (&XR)[NXF], bf16x8_t (&X0)[NXF], bf16x8_t (&X1)[NXF],
-                                            f32x16_t (&acc)[NGT][NXF]) {
+                                            typename WStream<W8>::type wp, typename WStream<W8>::type wpr,
+                                            int64_t wstride, xchunk_t xin, const uint32_t (&xp)[NXF + RIDER],
+                                            typename WFrag<W8>::type (&wq)[NGT][PW],
+                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
+                                            u32x4_t (&XR)[NXF + RIDER], bf16x8_t (&X0)[NXF + RIDER],
+                                            bf16x8_t (&X1)[NXF + RIDER], f32x16_t (&acc)[NGT][NXF],
+                                            f32x16_t (&accr)[1][1]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
-    const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8);
+    // (in 16-byte chunks, like the row offsets xp)
+    const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8) >> 3;
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, NGT, (U * 4 + 0) % PW, PW, 0, W8>(xs + 32, ks * 4 + 0, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 1) % PW, PW, 1, W8>(xs + 64, ks * 4 + 1, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER>(xs + 32, ks * 4 + 0, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER>(xs + 64, ks * 4 + 1, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
     __syncthreads();
-    packed_step<NXF, NGT, (U * 4 + 2) % PW, PW, 2, W8>(xs + 96, ks * 4 + 2, ksteps, wp, wstride, wq, X0, X1, acc, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 3) % PW, PW, 2, W8>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wstride, wq, X1, X0, acc, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER>(xs + 96, ks * 4 + 2, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
 }
 
-// One tile with NXF live 32-row activation fragments.
-template <bool GATEUP, int NXF, int NGT, bool W8>
-__device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, unsigned char *smem,
-                                            int K, int N, int ngroups, int nk4, int32_t lo_pos) {
+// Epilogue of NF accumulator fragments x NGT column groups, which are the rows of tile t from
+// its first on and the groups from group0 on.  Accumulator element v of lane l belongs to
+// weight row (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of the
+// fragment: for each block vg of 8 output columns a lane holds 4 of them and lane l ^ 32 the
+// other 4 of the same row.  Two blocks at a time, the halves of the wave trade pieces
+// (v_permlane32_swap: the upper half of the first operand against the lower half of the
+// second), after which the lower half owns all 8 columns of the first block and the upper
+// half those of the second: 16-byte stores, half as many as 8-byte ones would be.
+template <bool GATEUP, int NGT, int NF, bool W8>
+__device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t, const f32x16_t (&acc)[NGT][NF],
+                                                const float *wscale, int group0, int N, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
-    constexpr int PW = ring_depth(NXF);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lr = tid >> 3, kc = tid & 7;
-    const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
-    const int ksteps = nk4 * 16;
-    const int group0 = t.n0 / GC + wave * NGT;     // this wave's first column group
-    const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
-    // step-major stream: the fragments of all column groups for one step are adjacent.
-    // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
-    // of a tile has a stream to read even past the last real column.
-    const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
-    typename WStream<W8>::type wp = (typename WStream<W8>::type)wbase + (int64_t)group0 * 64 + lane;
-    const int64_t wstride = (int64_t)groups_padded * 64;
-    const unsigned short *xin = static_cast<const unsigned short *>(GATEUP ? a.x : a.act);
-
-    const unsigned short *xp[NXF];
-#pragma unroll
-    for (int i = 0; i < NXF; ++i) {
-        const int rr = min(lr + 32 * i, t.rows - 1);
-        const int32_t pos = t.pos0 + t.m0 + rr;
-        if (GATEUP) xp[i] = xin + (int64_t)(a.src[pos] / a.k) * K;
-        else xp[i] = xin + (int64_t)(pos - lo_pos) * K;
-    }
-
-    f32x16_t acc[NGT][NXF];
-#pragma unroll
-    for (int n = 0; n < NGT; ++n)
-#pragma unroll
-        for (int g = 0; g < NXF; ++g)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[n][g][v] = 0.0f;
-
-    // Request order: half the weight ring, the first two activation slabs, the other half of
-    // the ring.  The second slab is then followed by as many weight requests as in the loop,
-    // so the in-order load counter need not be drained when the loop is entered.
-    typename WFrag<W8>::type wq[NGT][PW];
-    u32x4_t xr[NXF];
-    {
-        u32x4_t xfirst[NXF];
-#pragma unroll
-        for (int j = 0; j < PW / 2; ++j)
-#pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
-        const int k0 = min(kc * 8, K - 8), k1 = min(64 + kc * 8, K - 8);
-#pragma unroll
-        for (int i = 0; i < NXF; ++i) xfirst[i] = *(xchunk_t)(xp[i] + k0);
-#pragma unroll
-        for (int i = 0; i < NXF; ++i) xr[i] = *(xchunk_t)(xp[i] + k1);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = PW / 2; j < PW; ++j)
-#pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NXF; ++i)
-            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xfirst[i];
-    }
-    __syncthreads();
-
-    bf16x8_t x0[NXF], x1[NXF];
-#pragma unroll
-    for (int g = 0; g < NXF; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 32 * XROWB);
-
-    const int last_slab = nk4 * 4 - 1;
-    int st = 0;                                    // LDS stage of the current slab
-    for (int ks = 0; ks <= last_slab; ks += 4) {
-        unsigned char *s0 = smem + st * XSTAGEB;
-        unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
-        unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
-        packed_slab<NXF, NGT, 0, PW, W8>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 1, PW, W8>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 2, PW, W8>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        packed_slab<NXF, NGT, 3, PW, W8>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wstride, xp, wq, xr, x0, x1, acc);
-        st = (st + 1) % 3;
-    }
-
-    // epilogue.  Accumulator element v of lane l belongs to weight row
-    // (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of fragment g: for each
-    // block vg of 8 output columns a lane holds 4 of them and lane l ^ 32 the other 4 of the same
-    // row.  Two blocks at a time, the halves of the wave trade pieces (v_permlane32_swap: the
-    // upper half of the first operand against the lower half of the second), after which the
-    // lower half owns all 8 columns of the first block and the upper half those of the second:
-    // 16-byte stores, half as many as 8-byte ones would be.
+    const int lane = threadIdx.x & 63;
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
-    // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows, then
-    // up rows; or down rows) and multiplies the accumulator of that output column
-    const float *wscale = reinterpret_cast<const float *>(
-        static_cast<const unsigned char *>(wbase) + (size_t)groups_padded * ksteps * 512);
 #pragma unroll
     for (int n = 0; n < NGT; ++n) {
         const int cbase = (group0 + n) * GC;
         constexpr int NVG = GATEUP ? 2 : 4;        // blocks of 8 output columns per group
-        // the scales depend on the column only: fetched once per group, not once per fragment
+        // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows,
+        // then up rows; or down rows) and multiplies the accumulator of that output column.
+        // The scales depend on the column only: fetched once per group, not once per fragment.
         float sa[NVG][4], sb[NVG][4];
 #pragma unroll
         for (int vg = 0; vg < NVG; ++vg)
@@ -250,7 +201,7 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
             }
         }
 #pragma unroll
-        for (int g = 0; g < NXF; ++g) {
+        for (int g = 0; g < NF; ++g) {
             const int m = g * 32 + (lane & 31);
             unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
             // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
@@ -281,6 +232,120 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, uns
     }
 }
 
+// One tile with NXF live 32-row activation fragments of its own slot and, with RIDER, one more
+// fragment of a cold slot (tile r: up to 32 rows, half a column tile starting at r.n0) that
+// meets one column group of that slot's weights per wave.
+template <bool GATEUP, int NXF, int NGT, bool W8, bool RIDER>
+__device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, const Tile &r, unsigned char *smem,
+                                            int K, int N, int ngroups, int nk4, int32_t lo_pos) {
+    constexpr int GC = GATEUP ? 16 : 32;
+    constexpr int NXA = NXF + (RIDER ? 1 : 0);
+    constexpr int PW = ring_depth(NXA);
+    // The lane's constants (LDS offsets and the like) are derived afresh in every tile: hoisted
+    // out of the tile loop they would stay live through the tallest tile, which has no
+    // register to spare, and come back from scratch inside every contraction loop.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lr = tid >> 3, kc = tid & 7;
+    const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
+    const int ksteps = nk4 * 16;
+    const int group0 = t.n0 / GC + wave * NGT;     // this wave's first column group
+    const int group_r = r.n0 / GC + wave;          // and its one group of the rider
+    const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
+    const void *wbase_r = RIDER ? (GATEUP ? a.wp_gateup[r.slot] : a.wp_down[r.slot]) : wbase;
+    // step-major stream: the fragments of all column groups for one step are adjacent.
+    // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
+    // of a tile has a stream to read even past the last real column.
+    const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
+    typename WStream<W8>::type wp = (typename WStream<W8>::type)wbase + (int64_t)group0 * 64 + lane;
+    typename WStream<W8>::type wpr = (typename WStream<W8>::type)wbase_r + (int64_t)group_r * 64 + lane;
+    const int64_t wstride = (int64_t)groups_padded * 64;
+    // activation rows as offsets in 16-byte chunks from the start of the matrix: 32 bits per
+    // row instead of a pointer (the host checks that the matrix has fewer than 2^32 chunks)
+    xchunk_t xin = (xchunk_t)(GATEUP ? a.x : a.act);
+    const uint32_t kchunks = (uint32_t)K >> 3;
+    uint32_t xp[NXA];
+#pragma unroll
+    for (int i = 0; i < NXA; ++i) {
+        const bool own = i < NXF;
+        const int rr = own ? min(lr + 32 * i, t.rows - 1) : min(lr, r.rows - 1);
+        const int32_t pos = own ? t.pos0 + t.m0 + rr : r.pos0 + r.m0 + rr;
+        xp[i] = (uint32_t)(GATEUP ? a.src[pos] / a.k : pos - lo_pos) * kchunks;
+    }
+
+    f32x16_t acc[NGT][NXF], accr[1][1];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accr[0][0][v] = 0.0f;
+#pragma unroll
+    for (int n = 0; n < NGT; ++n)
+#pragma unroll
+        for (int g = 0; g < NXF; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[n][g][v] = 0.0f;
+
+    // Request order: half the weight rings, the first two activation slabs, the other half of
+    // the rings.  The second slab is then followed by as many weight requests as in the loop,
+    // so the in-order load counter need not be drained when the loop is entered.
+    typename WFrag<W8>::type wq[NGT][PW], wr[RIDER ? rider_ring(NXF, W8) : 1];
+    u32x4_t xr[NXA];
+    {
+        u32x4_t xfirst[NXA];
+#pragma unroll
+        for (int j = 0; j < PW / 2; ++j)
+#pragma unroll
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
+        if (RIDER)
+#pragma unroll
+            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wpr[j * wstride];
+        if (!RIDER) wr[0] = zero_fragment<W8>();    // a placeholder that no MFMA reads
+        const int k0 = min(kc * 8, K - 8) >> 3, k1 = min(64 + kc * 8, K - 8) >> 3;
+#pragma unroll
+        for (int i = 0; i < NXA; ++i) xfirst[i] = xin[(size_t)xp[i] + k0];
+#pragma unroll
+        for (int i = 0; i < NXA; ++i) xr[i] = xin[(size_t)xp[i] + k1];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = PW / 2; j < PW; ++j)
+#pragma unroll
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
+        if (RIDER)
+#pragma unroll
+            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wpr[j * wstride];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NXA; ++i)
+            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xfirst[i];
+    }
+    __syncthreads();
+
+    bf16x8_t x0[NXA], x1[NXA];
+#pragma unroll
+    for (int g = 0; g < NXA; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 32 * XROWB);
+
+    const int last_slab = nk4 * 4 - 1;
+    int st = 0;                                    // LDS stage of the current slab
+    for (int ks = 0; ks <= last_slab; ks += 4) {
+        unsigned char *s0 = smem + st * XSTAGEB;
+        unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
+        unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
+        packed_slab<NXF, NGT, 0, PW, W8, RIDER>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 1, PW, W8, RIDER>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 2, PW, W8, RIDER>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 3, PW, W8, RIDER>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        st = (st + 1) % 3;
+    }
+
+    const size_t scale_off = (size_t)groups_padded * ksteps * 512;   // E4M3: row scales behind the codes
+    store_fragments<GATEUP, NGT, NXF, W8>(
+        a, t, acc, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase) + scale_off),
+        group0, N, lo_pos);
+    if (RIDER)
+        store_fragments<GATEUP, 1, 1, W8>(
+            a, r, accr, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase_r) + scale_off),
+            group_r, N, lo_pos);
+}
+
 template <bool GATEUP, bool W8>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
@@ -297,40 +362,82 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     const int nt = (N + BN - 1) / BN;
     const int nk4 = (K + 255) / 256;               // groups of four 64-wide slabs
     // The tile list: the busy slots' tiles (row-tiles x nt column tiles each, found through
-    // mt_start), then the cold slots' (one row-tile, 2 nt half-width column tiles each).
+    // mt_start), the first `carried` of them with a rider unit each, then what is left of the
+    // cold slots' units as tiles of their own (one row-tile, 2 nt half-width column tiles per
+    // slot).  Units are counted over the cold slots in list order: a two-fragment slot has
+    // 4 nt (fragment-major), a one-fragment slot 2 nt.
     const int32_t hot = a.ctrl[CTRL_HOT_SLOTS], live = a.ctrl[CTRL_LIVE_SLOTS];
+    const int32_t cold2 = a.ctrl[CTRL_COLD2_SLOTS];
+    const int64_t carried = a.ctrl[GATEUP ? CTRL_RIDERS_GATEUP : CTRL_RIDERS_DOWN];
+    const int64_t units2 = (int64_t)cold2 * 4 * nt;
     const int64_t hot_tiles = (int64_t)mt_start[hot] * nt;
-    const int64_t total = hot_tiles + (int64_t)(live - hot) * 2 * nt;
+    const int64_t cold_tiles = carried <= units2 ? (int64_t)(live - hot) * 2 * nt - carried / 2
+                                                 : (int64_t)(live - hot - cold2) * 2 * nt - (carried - units2);
+    const int64_t total = hot_tiles + cold_tiles;
     const int32_t lo_pos = a.slot_off[a.s_lo];
     const int32_t fmax = GATEUP ? a.frags_gu : a.frags_dn;
     int32_t *counter = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
+    // whole slot at position pos of the busiest-first order, as a tile
+    auto slot_tile = [&](int32_t pos) {
+        Tile t;
+        t.slot = small ? tt.order[pos] : a.order[pos];
+        t.pos0 = small ? tt.slot_off[t.slot] : a.slot_off[a.s_lo + t.slot];
+        t.rows = (small ? tt.slot_off[t.slot + 1] : a.slot_off[a.s_lo + t.slot + 1]) - t.pos0;
+        t.m0 = 0;
+        t.n0 = 0;
+        t.mtile = 0;
+        return t;
+    };
 
     int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
         if (w < hot_tiles) {
             const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
-            switch ((t.rows + 31) >> 5) {          // live 32-row fragments of this tile
-                case 1: packed_tile<GATEUP, 1, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 2: packed_tile<GATEUP, 2, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 3: packed_tile<GATEUP, 3, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 4: packed_tile<GATEUP, 4, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 5: packed_tile<GATEUP, 5, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 6: packed_tile<GATEUP, 6, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                case 7: packed_tile<GATEUP, 7, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                default: packed_tile<GATEUP, 8, NG, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos); break;
+            const int frags = (t.rows + 31) >> 5;  // live 32-row fragments of this tile
+            Tile r = t;
+            bool ride = w < carried && frags <= kRiderHostFrags;
+            if (ride) {                            // unit w: which cold slot, fragment and half column tile
+                const int64_t v = w < units2 ? w : w - units2;
+                r = slot_tile(hot + (int32_t)(w < units2 ? v / (4 * nt) : cold2 + v / (2 * nt)));
+                r.m0 = w < units2 ? (int32_t)(v % (4 * nt) / (2 * nt)) * 32 : 0;
+                r.rows = min(32, r.rows - r.m0);
+                r.n0 = (int32_t)(v % (2 * nt)) * (BN / 2);
+                ride = r.n0 < N;                   // the last half may lie past the matrix
+            }
+            if (ride) {
+                switch (frags) {
+                    case 1: packed_tile<GATEUP, 1, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 2: packed_tile<GATEUP, 2, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 3: packed_tile<GATEUP, 3, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 4: packed_tile<GATEUP, 4, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 5: packed_tile<GATEUP, 5, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 6: packed_tile<GATEUP, 6, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    default: packed_tile<GATEUP, 7, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                }
+            } else {
+                switch (frags) {
+                    case 1: packed_tile<GATEUP, 1, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 2: packed_tile<GATEUP, 2, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 3: packed_tile<GATEUP, 3, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 4: packed_tile<GATEUP, 4, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 5: packed_tile<GATEUP, 5, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 6: packed_tile<GATEUP, 6, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 7: packed_tile<GATEUP, 7, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    default: packed_tile<GATEUP, 8, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                }
             }
         } else {
+            // what the riders left: whole slots (both fragments in one tile) while inside the
+            // two-fragment slots, single units after them
             const int64_t cw = w - hot_tiles;
-            const int32_t pos = hot + (int32_t)(cw / (2 * nt));
-            Tile t;
-            t.slot = small ? tt.order[pos] : a.order[pos];
-            t.pos0 = small ? tt.slot_off[t.slot] : a.slot_off[a.s_lo + t.slot];
-            t.rows = (small ? tt.slot_off[t.slot + 1] : a.slot_off[a.s_lo + t.slot + 1]) - t.pos0;
-            t.m0 = 0;
-            t.n0 = (int32_t)(cw % (2 * nt)) * (BN / 2);
+            const int64_t v = carried <= units2 ? cw : cw + (carried - units2);
+            const int32_t c = carried <= units2 ? (int32_t)(carried / (4 * nt) + v / (2 * nt))
+                                                : cold2 + (int32_t)(v / (2 * nt));
+            Tile t = slot_tile(hot + c);
+            t.n0 = (int32_t)(v % (2 * nt)) * (BN / 2);
             if (t.n0 < N) {                        // the last half may lie past the matrix
-                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos);
-                else packed_tile<GATEUP, 2, 1, W8>(a, t, smem, K, N, ngroups, nk4, lo_pos);
+                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
+                else packed_tile<GATEUP, 2, 1, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
             }
         }
         if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);

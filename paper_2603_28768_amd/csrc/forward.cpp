@@ -103,39 +103,49 @@ int cached_num_cu() {
 // full load; replayed against measured sweeps of the height on three workloads the model
 // picks the fastest or second-fastest height each time.
 double ffn_makespan(const std::vector<double> &slot_rows, int32_t frags, bool even, int64_t nt,
-                    double fixed_us, double frag_us, int32_t cus) {
-    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
-    for (int32_t i = 0; i < cus; ++i) free_at.push(0.0);
-    double end = 0.0;
+                    double fixed_us, double frag_us, bool riders, double rider_us, int32_t cus) {
+    // the tile list as the kernel walks it: busy slots first (rows sorted, busiest first)
+    std::vector<double> cost;
+    int64_t ncold = 0, ncold2 = 0;
     for (double r : slot_rows) {
         const int64_t F = (int64_t)((r + 31.0) / 32.0);
         if (F <= 0) continue;
-        if (r <= (double)kColdRows) {              // cold slot: half-width tiles, about half the cost
-            for (int64_t n = 0; n < 2 * nt; ++n) {
-                const double t = free_at.top() + 4.0 + 0.5 * (fixed_us + frag_us * (double)F);
-                free_at.pop();
-                free_at.push(t);
-                end = std::max(end, t);
-            }
-            continue;
-        }
+        if (r <= (double)kColdRows) { ncold += 1; ncold2 += F > 1 ? 1 : 0; continue; }
         const int64_t m = (F + frags - 1) / frags;
         for (int64_t n = 0; n < nt; ++n)
             for (int64_t i = 0; i < m; ++i) {
                 const int64_t f = even ? (i + 1) * F / m - i * F / m : std::min<int64_t>(frags, F - i * frags);
-                const double t = free_at.top() + fixed_us + frag_us * (double)f;
-                free_at.pop();
-                free_at.push(t);
-                end = std::max(end, t);
+                cost.push_back(fixed_us + frag_us * (double)f);
             }
+    }
+    // rider units go to the first tiles, one each (see kRiderHostFrags)
+    const int64_t units2 = ncold2 * 4 * nt, units = units2 + (ncold - ncold2) * 2 * nt;
+    int64_t carried = riders && frags <= kRiderHostFrags ? std::min<int64_t>((int64_t)cost.size(), units) : 0;
+    if (carried < units2) carried = carried / (4 * nt) * (4 * nt);
+    for (int64_t u = 0; u < carried; ++u) cost[(size_t)u] += rider_us;
+    // what is left of the cold slots: half-width tiles, about half the cost
+    const int64_t left2 = carried <= units2 ? ncold2 - carried / (4 * nt) : 0;
+    const int64_t left1 = carried <= units2 ? (ncold - ncold2) * 2 * nt : units - carried;
+    for (int64_t i = 0; i < left2 * 2 * nt; ++i) cost.push_back(4.0 + 0.5 * (fixed_us + frag_us * 2.0));
+    for (int64_t i = 0; i < left1; ++i) cost.push_back(4.0 + 0.5 * (fixed_us + frag_us));
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int32_t i = 0; i < cus; ++i) free_at.push(0.0);
+    double end = 0.0;
+    for (double c : cost) {
+        const double t = free_at.top() + c;
+        free_at.pop();
+        free_at.push(t);
+        end = std::max(end, t);
     }
     return end;
 }
 
-std::pair<int32_t, int32_t> choose_tile_frags(const craft_plan_t *plan, int32_t layer, int32_t rank,
-                                              int64_t T, int32_t k, int32_t H, int32_t I, int32_t cus) {
+using tile_choice = craft_plan_t::tile_choice;
+
+tile_choice choose_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank, int64_t T, int32_t k,
+                         int32_t H, int32_t I, int32_t cus) {
     const craft_layer_plan &lp = plan->layers[layer];
-    std::pair<int32_t, int32_t> best{kFragsPacked, kFragsPacked};
+    tile_choice best{{kFragsPacked, kFragsPacked}, {false, false}};
     double total = 0.0;
     for (int64_t v : lp.expert_load) total += (double)v;
     if (total <= 0.0 || T <= 0) return best;
@@ -155,6 +165,10 @@ std::pair<int32_t, int32_t> choose_tile_frags(const craft_plan_t *plan, int32_t 
         // per-tile device timestamps at K = 4096 and 7168 (gate/up) and 1536 and 2048 (down)
         const double fixed_us = kind == 0 ? 20.0 + 0.0055 * (double)K : 21.0 + 0.0020 * (double)K;
         const double frag_us = kind == 0 ? 1.5 + 0.00182 * (double)K : 0.1 + 0.00234 * (double)K;
+        // A rider's weights come through the same path from L2 as the tile's own operands, and
+        // that path is what bounds a tile under full load: the rider costs its bytes (5 KB per
+        // step against the tile's 8 + fragments) rather than its one MFMA in 2 * fragments + 1.
+        const double rider_us = 4.0 + 0.004 * (double)K;
         // Only where the busy slots' tiles make up a round or two does their count decide the
         // time; over many rounds the tallest tile (most reuse per weight fragment, fewest
         // fixed costs) wins by itself, and there the model is not trusted to say otherwise.
@@ -164,32 +178,40 @@ std::pair<int32_t, int32_t> choose_tile_frags(const craft_plan_t *plan, int32_t 
         if (tall_tiles > 2 * (int64_t)cus) continue;
         double best_t = 0.0;
         for (int32_t f = kFragsPacked; f >= 4; --f)
-            for (int even = 0; even < 2; ++even) {
-                const double t = ffn_makespan(rows, f, even != 0, nt, fixed_us, frag_us, cus);
-                if ((f == kFragsPacked && !even) || t < best_t * 0.98) {    // a change has to earn it
-                    best_t = t;
-                    (kind == 0 ? best.first : best.second) = even ? -f : f;
+            for (int even = 0; even < 2; ++even)
+                for (int riders = 0; riders < (f <= kRiderHostFrags ? 2 : 1); ++riders) {
+                    const double t = ffn_makespan(rows, f, even != 0, nt, fixed_us, frag_us, riders != 0, rider_us, cus);
+                    if ((f == kFragsPacked && !even) || t < best_t * 0.98) {    // a change has to earn it
+                        best_t = t;
+                        best.frags[kind] = even ? -f : f;
+                        best.riders[kind] = riders != 0;
+                    }
                 }
-            }
     }
     return best;
 }
 
-std::pair<int32_t, int32_t> tile_frags_for(const craft_plan_t *plan, int32_t layer, int32_t rank,
-                                           const craft_fwd_args *a, bool packed) {
-    if (a->dtype != CRAFT_BF16) return {kFragsF32, kFragsF32};
-    if (!packed) return {kFragsBf16, kFragsBf16};
+tile_choice tiles_for(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a,
+                      bool packed) {
+    if (a->dtype != CRAFT_BF16) return {{kFragsF32, kFragsF32}, {false, false}};
+    if (!packed) return {{kFragsBf16, kFragsBf16}, {false, false}};
     craft_plan_t *p = const_cast<craft_plan_t *>(plan);
     const std::array<int64_t, 6> key{layer, rank, a->T, a->k, a->H, a->I};
     std::lock_guard<std::mutex> lk(p->reg_mutex);
     auto it = p->tile_cache.find(key);
     if (it == p->tile_cache.end())
-        it = p->tile_cache.emplace(key, choose_tile_frags(plan, layer, rank, a->T, a->k, a->H, a->I,
-                                                           cached_num_cu())).first;
-    std::pair<int32_t, int32_t> f = it->second;
-    if (a->tile_rows_gateup) f.first = a->tile_rows_gateup / 32;      // the caller's own choice
-    if (a->tile_rows_down) f.second = a->tile_rows_down / 32;
-    return f;
+        it = p->tile_cache.emplace(key, choose_tiles(plan, layer, rank, a->T, a->k, a->H, a->I,
+                                                     cached_num_cu())).first;
+    tile_choice c = it->second;
+    // the caller's own heights: riders wherever such tiles can carry them, unless told
+    const int32_t rows_arg[2] = {a->tile_rows_gateup, a->tile_rows_down};
+    const int32_t riders_arg[2] = {a->riders_gateup, a->riders_down};
+    for (int kind = 0; kind < 2; ++kind) {
+        if (rows_arg[kind]) { c.frags[kind] = rows_arg[kind] / 32; c.riders[kind] = true; }
+        if (riders_arg[kind]) c.riders[kind] = riders_arg[kind] > 0;
+        c.riders[kind] = c.riders[kind] && std::abs(c.frags[kind]) <= kRiderHostFrags;
+    }
+    return c;
 }
 
 craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a) {
@@ -199,6 +221,8 @@ craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, co
     if (plan->E > 1024 || a->max_rows < 0) return CRAFT_EINVAL;
     for (int32_t r : {a->tile_rows_gateup, a->tile_rows_down})
         if (r != 0 && (r % 32 || r < 128 || r > 256)) return CRAFT_EINVAL;
+    for (int32_t r : {a->riders_gateup, a->riders_down})
+        if (r < -1 || r > 1) return CRAFT_EINVAL;
     if (a->T * (int64_t)a->k >= ((int64_t)1 << 31)) return CRAFT_EINVAL;
     const int unit = a->dtype == CRAFT_BF16 ? 8 : 4;
     if (a->H % unit || a->I % unit) return CRAFT_EINVAL;
@@ -355,6 +379,10 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
         if (a->weight_format != CRAFT_W_BF16 && a->weight_format != CRAFT_W_E4M3) return CRAFT_EINVAL;
         if (a->weight_format == CRAFT_W_E4M3 && !packed) return CRAFT_EINVAL;
         if (nslots > 0 && !packed && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
+        // the packed kernels address activation rows by 32-bit offsets in 16-byte chunks
+        const int64_t chunk_limit = (int64_t)1 << 32;
+        if (packed && (a->T * (int64_t)a->H / 8 >= chunk_limit || L.max_rows * (int64_t)a->I / 8 >= chunk_limit))
+            return CRAFT_EINVAL;
     }
     hipStream_t s = as_stream(stream);
     unsigned char *ws = static_cast<unsigned char *>(a->workspace);
@@ -371,7 +399,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     int32_t *mt_start = reinterpret_cast<int32_t *>(ws + L.mt_start);
     int32_t *order = reinterpret_cast<int32_t *>(ws + L.order);
     const bool packed = a->w_gateup_packed && a->w_down_packed;
-    const std::pair<int32_t, int32_t> frags = tile_frags_for(plan, layer, rank, a, packed);
+    const tile_choice tiles = tiles_for(plan, layer, rank, a, packed);
     const int32_t *tables = static_cast<const int32_t *>(a->tables);
 
     // 1 route (+ per-block ranks and counts); user copies of ids / weights are written by the
@@ -386,8 +414,9 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 2 per-expert totals, slot offsets, tile table
     {
         ScopedEvent ev(CRAFT_K_SCAN, s);
-        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi, frags.first, frags.second, L.max_rows,
-                    counts, slot_cnt, slot_off, mt_start, order, ctrl,
+        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi, tiles.frags[0], tiles.frags[1], L.max_rows,
+                    counts, slot_cnt, slot_off, mt_start, order, tiles.riders[0] ? (a->I + 127) / 128 : 0,
+                    tiles.riders[1] ? (a->H + 255) / 256 : 0, ctrl,
                     a->counts, a->slot_cnt, a->slot_off};
         if (launch_scan(sa, s) != hipSuccess) return CRAFT_EHIP;
     }
@@ -401,7 +430,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     FfnArgs fa{a->dtype, a->H, a->I, a->k, s_lo, nslots, a->x, src, slot_off, mt_start, order, ctrl,
                a->w_gate, a->w_up, a->w_down, a->w_gateup_packed, a->w_down_packed,
                ws + L.act, ws + L.y, L.max_rows, cached_num_cu(), a->weight_format == CRAFT_W_E4M3 ? 1 : 0,
-               frags.first, frags.second};
+               tiles.frags[0], tiles.frags[1]};
     if (a->T > 0) {
         {
             ScopedEvent ev(CRAFT_K_GATEUP, s);
@@ -425,13 +454,16 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
 
 craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                           const craft_fwd_args *a, int32_t *rows_gateup,
-                                          int32_t *rows_down) {
+                                          int32_t *rows_down, int32_t *riders_gateup,
+                                          int32_t *riders_down) {
     craft_status st = check_fwd(plan, layer, rank, a);
     if (st != CRAFT_OK) return st;
     const bool packed = a->w_gateup_packed && a->w_down_packed;
-    const std::pair<int32_t, int32_t> f = tile_frags_for(plan, layer, rank, a, packed);
-    if (rows_gateup) *rows_gateup = 32 * std::abs(f.first);
-    if (rows_down) *rows_down = 32 * std::abs(f.second);
+    const tile_choice c = tiles_for(plan, layer, rank, a, packed);
+    if (rows_gateup) *rows_gateup = 32 * std::abs(c.frags[0]);
+    if (rows_down) *rows_down = 32 * std::abs(c.frags[1]);
+    if (riders_gateup) *riders_gateup = c.riders[0] ? 1 : 0;
+    if (riders_down) *riders_down = c.riders[1] ? 1 : 0;
     return CRAFT_OK;
 }
 

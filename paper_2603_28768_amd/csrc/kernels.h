@@ -19,6 +19,8 @@ enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
        CTRL_WORK_GATEUP = 4, CTRL_WORK_DOWN = 5,   // dynamic tile counters of the two GEMMs
        CTRL_HOT_SLOTS = 6,                         // slots of the rank with more than kColdRows rows
        CTRL_LIVE_SLOTS = 7,                        // slots of the rank with any rows
+       CTRL_RIDERS_GATEUP = 8, CTRL_RIDERS_DOWN = 9,   // rider units carried by the busy slots' tiles, per GEMM
+       CTRL_COLD2_SLOTS = 10,                      // cold slots with two fragments (33 .. kColdRows rows)
        CTRL_WORDS = 16 };
 
 // A slot with at most this many rows is "cold": its tiles do next to no matrix work and are
@@ -26,6 +28,18 @@ enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
 // many, half as long), because what the tail of a launch costs is the length of a cold tile
 // and the aggregate weight bandwidth grows with the number of CUs streaming at once.
 constexpr int kColdRows = 64;
+
+// Riders.  During a tile of a busy slot the CU's matrix pipeline is busy and HBM is not;
+// during a cold slot's tile it is the other way round.  So a tile of a busy slot carries a
+// "rider unit" along: one 32-row fragment of a cold slot against half a column tile of that
+// slot's weights (one column group per wave), streamed through a second weight ring and
+// costing one more MFMA per step.  Half a tile, not a whole one, because a CU's vector
+// memory path (64 bytes per clock) is already two-thirds used by the tile's own operands.
+// The units of the cold slots, in busiest-first order (two-fragment slots first), go to the
+// tiles of the list one each, from the first tile on: unit u rides on tile u.  A two-fragment
+// slot is carried whole or not at all.  Tiles of more than kRiderHostFrags fragments have no
+// registers left for a rider: a launch with taller tiles carries none.
+constexpr int kRiderHostFrags = 7;
 
 // Most 32-row fragments a row-tile of the grouped GEMMs may have (the tile table is built for
 // a height chosen per launch, up to these).
@@ -59,6 +73,7 @@ struct ScanArgs {
     int32_t *mt_start;        // [2][s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot
                               // first: for the gate/up GEMM, then for the down GEMM
     int32_t *order;           // [s_hi - s_lo] local slot at each position of that order
+    int32_t nt_gu, nt_dn;     // column tiles per slot of the two packed GEMMs; 0: no riders
     int32_t *ctrl;
     int32_t *user_counts, *user_slot_cnt, *user_slot_off;   // optional copies
 };

@@ -38,8 +38,10 @@ struct craft_plan {
     int32_t auto_R = 0;                  // replication factor picked in automatic mode
     std::mutex reg_mutex;
     std::vector<craft_table_reg> regs;   // device table buffers filled from this plan
-    // FFN row-tile heights chosen for (layer, rank, T, k, H, I): fragments for gate/up, down
-    std::map<std::array<int64_t, 6>, std::pair<int32_t, int32_t>> tile_cache;
+    // FFN tile choices made for (layer, rank, T, k, H, I): for gate/up and down, the fragments
+    // per row-tile (negative: shared evenly) and whether cold slots ride along with busy tiles
+    struct tile_choice { int32_t frags[2]; bool riders[2]; };
+    std::map<std::array<int64_t, 6>, tile_choice> tile_cache;
 };
 
 // Device tables of one (layer, rank): a header followed by int32 arrays, all offsets in

@@ -85,9 +85,11 @@ def test_expert_load_on_a_zipf_trace(torch_cuda):
 
 # --------------------------------------------------------------------- forward
 
-def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False):
+def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False, knobs=None):
     cfg = case.cfg
     fwd, x, logits = case.gpu_rank(rank, max_rows, packed=packed)
+    for name, value in (knobs or {}).items():          # tuning knobs of the packed FFN
+        setattr(fwd.args, name, value)
     out = fwd(x, logits)
     rows, ovf = fwd.result()
     ref = case.oracle_rank(rank, tokens)
@@ -243,6 +245,33 @@ def test_forward_rejects_foreign_tables(torch_cuda):
     fwd.args.tables = x.data_ptr()                                  # not a table buffer at all
     with pytest.raises(binding.CraftError):
         fwd(x, logits)
+
+
+@pytest.mark.parametrize("w8", [False, True])
+@pytest.mark.parametrize("T,H,I,E,k,D,slots,zipf", [
+    (240, 128, 192, 32, 4, 1, 0, 1.0),     # fewer busy tiles than units of the two-fragment slots
+    (400, 128, 64, 48, 6, 1, 0, 1.5),      # more units than busy tiles: some cold tiles remain
+    (900, 256, 320, 32, 4, 2, 2, 1.8)])    # three column tiles, replicas
+def test_cold_slots_riding_with_busy_tiles(torch_cuda, T, H, I, E, k, D, slots, zipf, w8):
+    # slots with at most 64 rows are carried by the tiles of busy slots or get tiles of their
+    # own: every way of cutting the work gives the same bits, and those match the checker
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=T, H=H, I=I, E=E, k=k, D=D, replica_slots=slots,
+                       zipf_s=zipf, profile_batches=2)
+    case = Case(cfg, w8=w8)
+    for g in range(D):
+        rows = case.slot_cnt[case.rank_slot_off[g]:case.rank_slot_off[g + 1]]
+        assert (rows > 64).any() and ((rows > 0) & (rows <= 32)).any()
+        if D == 1:
+            assert ((rows > 32) & (rows <= 64)).any()
+        outs = []
+        for knobs in (dict(riders_gateup=-1, riders_down=-1),
+                      dict(tile_rows_gateup=128, tile_rows_down=160, riders_gateup=1, riders_down=1),
+                      dict(tile_rows_gateup=224, tile_rows_down=224, riders_gateup=1, riders_down=-1),
+                      dict(tile_rows_gateup=256, tile_rows_down=192, riders_gateup=1, riders_down=1)):
+            print(" ", knobs, flush=True)
+            outs.append(_check_rank(torch_cuda, case, g, packed=True, knobs=knobs)[0])
+        for o in outs[1:]:
+            assert np.array_equal(outs[0], o)
 
 
 # -------------------------------------------------- full-size configurations

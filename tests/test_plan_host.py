@@ -219,26 +219,43 @@ def test_stack_shape_three_planners_side_by_side():
 
 
 def test_ffn_tile_heights_query():
-    # host-side choice of the grouped-GEMM row-tile height; no device work
+    # host-side choice of the grouped-GEMM row-tile height and of riders; no device work
     lib = binding.lib()
     g = np.random.default_rng(3)
     W = g.multinomial(8 * 4096, synth.popularity(128, 1.0, 2, 0), size=(4, 1)).astype(np.int64)
     plan = binding.Plan(W, 8, 8)
     a = binding.FwdArgs()
     a.dtype, a.T, a.H, a.I, a.k = 1, 4096, 4096, 1536, 8
-    gu, dn = ctypes.c_int32(), ctypes.c_int32()
-    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 0, ctypes.byref(a), gu, dn) == 0
-    assert (gu.value, dn.value) == (128, 128)                  # row-major bf16 weights: fixed
+    gu, dn, rgu, rdn = (ctypes.c_int32() for _ in range(4))
+
+    def query(rank=0):
+        return lib.craft_moe_rank_forward_tiles(plan._h, 0, rank, ctypes.byref(a), gu, dn, rgu, rdn)
+
+    assert query() == 0
+    assert (gu.value, dn.value, rgu.value, rdn.value) == (128, 128, 0, 0)   # row-major bf16 weights: fixed
     a.w_gateup_packed = a.w_down_packed = 0x1000               # packed: chosen from the plan's loads
     for rank in range(8):
-        assert lib.craft_moe_rank_forward_tiles(plan._h, 0, rank, ctypes.byref(a), gu, dn) == 0
+        assert query(rank) == 0
         assert gu.value % 32 == 0 and 128 <= gu.value <= 256
         assert dn.value % 32 == 0 and 128 <= dn.value <= 256
-        first = (gu.value, dn.value)
-        assert lib.craft_moe_rank_forward_tiles(plan._h, 0, rank, ctypes.byref(a), gu, dn) == 0
-        assert (gu.value, dn.value) == first                   # kept with the plan
+        assert rgu.value in (0, 1) and rdn.value in (0, 1)
+        assert not (rgu.value and gu.value > 224) and not (rdn.value and dn.value > 224)
+        first = (gu.value, dn.value, rgu.value, rdn.value)
+        assert query(rank) == 0
+        assert (gu.value, dn.value, rgu.value, rdn.value) == first          # kept with the plan
+    # the caller's knobs win; the tallest tile has no room for a rider
+    a.tile_rows_gateup, a.tile_rows_down, a.riders_gateup, a.riders_down = 192, 256, -1, 1
+    assert query() == 0
+    assert (gu.value, dn.value, rgu.value, rdn.value) == (192, 256, 0, 0)
+    a.riders_gateup, a.tile_rows_down = 1, 224
+    assert query() == 0
+    assert (gu.value, dn.value, rgu.value, rdn.value) == (192, 224, 1, 1)
+    a.riders_down = 2
+    assert query() == -1
+    a.tile_rows_gateup = a.tile_rows_down = a.riders_gateup = a.riders_down = 0
+    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 0, ctypes.byref(a), gu, None, None, None) == 0
     a.dtype = 0
     a.w_gateup_packed = a.w_down_packed = None
-    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 0, ctypes.byref(a), gu, dn) == 0
-    assert (gu.value, dn.value) == (32, 32)
-    assert lib.craft_moe_rank_forward_tiles(plan._h, 0, 9, ctypes.byref(a), gu, dn) == -1
+    assert query() == 0
+    assert (gu.value, dn.value, rgu.value, rdn.value) == (32, 32, 0, 0)
+    assert query(9) == -1
