@@ -44,6 +44,8 @@ def _load():
         lib.oracle_dispatch.argtypes = [vp, c_i64, c_i32, c_i32, vp, vp, vp, vp, vp]
         lib.oracle_ffn_rows.argtypes = [vp, c_i64, c_i32, c_i32, vp, vp, vp, vp]
         lib.oracle_combine.argtypes = [vp, c_i64, c_i64, vp, vp, c_i64, c_i32, c_i32, vp]
+        lib.oracle_router_logits.argtypes = [vp, vp, c_i64, c_i32, c_i32, vp]
+        lib.oracle_router_logits.restype = ctypes.c_int
         lib.oracle_quantize_e4m3.argtypes = [vp, c_i64, c_i64, vp, vp]
         lib.oracle_quantize_e4m3.restype = ctypes.c_int
         lib.oracle_e4m3_value.argtypes = [ctypes.c_uint8]
@@ -65,6 +67,19 @@ def _c(a, dtype) -> np.ndarray:
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def router_logits(x: np.ndarray, w_router: np.ndarray) -> np.ndarray:
+    """fp32 scores [T][E] of the linear gate: x [T][H] against w_router [E][H]."""
+    x, w_router = _c(x, np.float32), _c(w_router, np.float32)
+    (T, H), (E, H2) = x.shape, w_router.shape
+    if H != H2:
+        raise ValueError("x and w_router disagree on the hidden size")
+    out = np.empty((T, E), dtype=np.float32)
+    rc = _load().oracle_router_logits(_p(x), _p(w_router), T, H, E, _p(out))
+    if rc:
+        raise ValueError(f"oracle_router_logits failed ({rc})")
+    return out
 
 
 def route(logits: np.ndarray, k: int, renormalize: bool = True) -> Tuple[np.ndarray, np.ndarray]:

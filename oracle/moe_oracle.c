@@ -10,6 +10,9 @@
  * representable in their storage type).
  *
  * What is computed, and where the paper defines it:
+ *   oracle_router_logits Sec. 2.1: "a lightweight gating network computes a score for
+ *                        each expert": read as the usual linear gate, score[t][e] =
+ *                        x[t] . W_r[e], no bias (the paper gives no form).
  *   oracle_route         Sec. 2.1: a gating network scores every expert, the
  *                        top-K scores are activated, outputs are weighted.
  *   oracle_expert_load   Sec. 3.1 "expert load" = tokens dispatched to an expert
@@ -35,6 +38,23 @@
 #ifdef _OPENMP
 #include <omp.h>
 #endif
+
+/* Sec. 2.1 gating network, linear form: logits[t][e] = sum_h x[t][h] * Wr[e][h], the sum
+ * taken in double over h ascending and rounded once to float.  x [T][H], Wr [E][H]. */
+int oracle_router_logits(const float *x, const float *Wr, int64_t T, int32_t H, int32_t E,
+                         float *logits)
+{
+    if (T < 0 || H <= 0 || E <= 0) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int32_t e = 0; e < E; ++e) {
+            const float *a = x + t * H, *b = Wr + (int64_t)e * H;
+            double s = 0.0;
+            for (int32_t h = 0; h < H; ++h) s += (double)a[h] * (double)b[h];
+            logits[t * E + e] = (float)s;
+        }
+    return 0;
+}
 
 /* Sec. 2.1 router.  ids[t][j] = expert with the (j+1)-th largest raw score of
  * token t (equal scores: lower expert id first).  w[t][j] = softmax probability
