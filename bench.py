@@ -17,6 +17,7 @@ from __future__ import annotations
 import argparse
 import hashlib
 import json
+import math
 import os
 import sys
 import time
@@ -179,6 +180,42 @@ def bench_trace_load(args):
     print(json.dumps(out), flush=True)
 
 
+def bench_gate(args, name):
+    """Secondary workload: craft_router_logits (the linear gating network) at the shape of a
+    layer configuration, activations and gate weights resident in HBM."""
+    import torch
+    from paper_2603_28768_amd import binding, synth
+    cfg = synth.CONFIGS[name]
+    g = torch.Generator(device="cuda").manual_seed(synth.BASE_SEED + 11)
+    x = torch.randn((cfg.T, cfg.H), generator=g, device="cuda").to(torch.bfloat16)
+    w = (torch.randn((cfg.E, cfg.H), generator=g, device="cuda") / math.sqrt(cfg.H)).to(torch.bfloat16)
+    for _ in range(args.warmup):
+        logits = binding.router_logits(x, w)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for _ in range(args.steps):
+        logits = binding.router_logits(x, w)
+    ev[1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = ev[0].elapsed_time(ev[1]) / args.steps         # the kernel runs on torch's current stream
+    assert bool(torch.isfinite(logits).all())
+    nbytes = x.numel() * 2 + w.numel() * 2 + logits.numel() * 4
+    flops = 2.0 * cfg.T * cfg.H * cfg.E
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    out = dict(metric="gating-network tokens/s on 1 GPU", value=cfg.T / (dt / args.steps), unit="tokens/s",
+               n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=dt / args.steps * 1e3,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload=f"linear gate at the {name} shape: T={cfg.T} H={cfg.H} E={cfg.E}"),
+               roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                             frac=gbs / HBM_PEAK_GBS, traffic=None, kernel="router_logits_bf16_kernel",
+                             avg_ms=ms, algorithmic_bytes=nbytes, algorithmic_flops=flops,
+                             achieved_tflops=flops / (ms * 1e-3) / 1e12))
+    print(json.dumps(out), flush=True)
+
+
 def copy_calibration(args):
     """A plain 256 MiB device-to-device copy: the known-size kernel against which the
     FETCH_SIZE / WRITE_SIZE counters are scaled, and the box's own copy bandwidth."""
@@ -263,6 +300,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="qwen3",
                     help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only) | "
+                         "gate_qwen3 | gate_dsv3 | gate_kimi (gating network only) | "
                          "copy_calib (plain copy for counter calibration) | "
                          "plan_curves (host only: balancedness vs budget for the three planners)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -288,6 +326,8 @@ def main():
         return bench_trace_load(args)
     if args.config == "copy_calib":
         return copy_calibration(args)
+    if args.config.startswith("gate_"):
+        return bench_gate(args, args.config[5:])
     cfg = synth.CONFIGS[args.config]
     e4m3 = args.weights == "e4m3"
     if e4m3:

@@ -44,6 +44,21 @@ const char *craft_status_str(craft_status s);
 /* Element types of activations and expert weights. */
 enum { CRAFT_F32 = 0, CRAFT_BF16 = 1 };
 
+/* -------------------------------------------------------------- gating network
+ * Sec. 2.1: for each token the gating network computes a score for each expert.  The paper
+ * gives the network no form; this is the usual linear gate without bias,
+ *   logits[t][e] = sum_h x[t][h] * w_router[e][h]   (fp32 accumulation, fp32 result).
+ *   dtype     CRAFT_F32 or CRAFT_BF16: element type of x and w_router
+ *   x         DEVICE [T][H], 16-byte aligned
+ *   w_router  DEVICE [E][H], 16-byte aligned
+ *   logits    DEVICE [T][E] fp32, fully overwritten; what craft_route_topk and
+ *             craft_moe_rank_forward take as their scores
+ * Limits: 1 <= E <= 1024, H >= 1, H % 8 == 0 for bf16.  T may be 0.  Asynchronous on
+ * `stream`; CRAFT_EINVAL on a bad size, a NULL or a misaligned pointer.
+ */
+craft_status craft_router_logits(int32_t dtype, const void *x, const void *w_router, int64_t T,
+                                 int32_t H, int32_t E, float *logits, void *stream);
+
 /* ------------------------------------------------------------------ routing
  * Sec. 2.1: the gating network's scores select the top-K experts of each token.
  *   logits  DEVICE [T][E] fp32 router scores

@@ -44,6 +44,7 @@ class FwdArgs(ctypes.Structure):
 
 EXPORTS = {
     "craft_status_str": (ctypes.c_char_p, [ctypes.c_int]),
+    "craft_router_logits": (ctypes.c_int, [c_i32, c_vp, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
     "craft_route_topk": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp]),
     "craft_expert_load": (ctypes.c_int, [c_vp, c_i32, c_i64, c_i32, c_i32, c_i64, c_vp, c_vp]),
     "craft_load_accumulate": (ctypes.c_int, [c_vp, c_i64, c_vp, c_vp]),
@@ -121,6 +122,21 @@ def _dev(t):
 
 
 # ------------------------------------------------------------------------ routing
+
+def router_logits(x, w_router, stream=None):
+    """x: cuda [T][H], w_router: cuda [E][H] (both float32 or both bfloat16) -> float32 [T][E]."""
+    import torch
+    assert x.dim() == 2 and w_router.dim() == 2 and x.shape[1] == w_router.shape[1]
+    assert x.dtype == w_router.dtype and x.dtype in (torch.float32, torch.bfloat16)
+    assert x.is_contiguous() and w_router.is_contiguous()
+    T, H = x.shape
+    E = w_router.shape[0]
+    logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
+    _check(lib().craft_router_logits(CRAFT_BF16 if x.dtype == torch.bfloat16 else CRAFT_F32, _dev(x),
+                                     _dev(w_router), T, H, E, _dev(logits), _stream_ptr(stream)),
+           "craft_router_logits")
+    return logits
+
 
 def route_topk(logits, k: int, renormalize: bool = True, stream=None):
     """logits: cuda float32 [T][E] -> (ids int32 [T][k], w float32 [T][k])."""

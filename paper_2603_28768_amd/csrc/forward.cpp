@@ -236,6 +236,18 @@ craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, co
 
 extern "C" {
 
+craft_status craft_router_logits(int32_t dtype, const void *x, const void *w_router, int64_t T,
+                                 int32_t H, int32_t E, float *logits, void *stream) {
+    if (dtype != CRAFT_F32 && dtype != CRAFT_BF16) return CRAFT_EINVAL;
+    if (T < 0 || H <= 0 || E <= 0 || E > 1024 || (dtype == CRAFT_BF16 && H % 8)) return CRAFT_EINVAL;
+    if (T * (int64_t)E >= ((int64_t)1 << 40)) return CRAFT_EINVAL;
+    if (T == 0) return CRAFT_OK;
+    if (!x || !w_router || !logits || !aligned(x, 16) || !aligned(w_router, 16) || !aligned(logits, 4))
+        return CRAFT_EINVAL;
+    RouterArgs ra{dtype, x, w_router, T, H, E, logits, cached_num_cu()};
+    return launch_router_logits(ra, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
+}
+
 craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t k,
                               int32_t renormalize, int32_t *ids, float *w, void *stream) {
     if (T < 0 || E <= 0 || E > 1024 || k <= 0 || k > E || k > 64) return CRAFT_EINVAL;

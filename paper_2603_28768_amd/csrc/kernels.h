@@ -48,6 +48,17 @@ constexpr int kFragsPacked = 8;    // weight-streaming bf16 kernels (packed weig
 constexpr int kFragsF32 = 1;
 constexpr int kBM_packed = kFragsPacked * 32;
 
+struct RouterArgs {
+    int32_t dtype;
+    const void *x;            // [T][H]
+    const void *w;            // [E][H] gate weights
+    int64_t T;
+    int32_t H, E;
+    float *logits;            // [T][E]
+    int32_t num_cu;
+};
+hipError_t launch_router_logits(const RouterArgs &a, hipStream_t s);
+
 struct RouteArgs {
     const float *logits;
     int64_t T;

@@ -127,6 +127,14 @@ def router_logits(cfg: LayerConfig, pop: np.ndarray, tag: str, batch: int = 0,
     return (z + np.log(pop).astype(np.float32)[None, :]).astype(np.float32)
 
 
+def gate_weights(cfg: LayerConfig, layer: int = 0) -> np.ndarray:
+    """W_router [E][H] of a linear gating network: N(0, 1/sqrt(H)), storage-rounded (scores of
+    unit-variance activations then have unit variance, like `router_logits` without its bias)."""
+    g = rng(cfg.index, "gate", layer)
+    w = g.standard_normal((cfg.E, cfg.H), dtype=np.float32) * np.float32(1.0 / math.sqrt(cfg.H))
+    return round_to_storage(w, cfg.dtype)
+
+
 def activations(cfg: LayerConfig, T: Optional[int] = None, layer: int = 0) -> np.ndarray:
     T = cfg.T if T is None else T
     g = rng(cfg.index, "x", layer)

@@ -83,6 +83,75 @@ def test_expert_load_on_a_zipf_trace(torch_cuda):
     assert np.all(got.sum(-1) == bt * k)
 
 
+# ------------------------------------------------------------- gating network
+
+# fp32 accumulation of H products against the checker's double sum: the running sum stays of
+# the size of the scores (a few units), each of the H/16 accumulator updates rounds it at
+# 2^-24 relative, so the error is a few 1e-7 of the score scale in practice and H * 2^-24 of
+# it at the very worst; 1e-4 of the largest score leaves room for both and is still a
+# hundred times finer than a dropped or doubled term.
+GATE_TOL = 1e-4
+
+
+@pytest.mark.parametrize("dtype,T,H,E", [
+    ("bf16", 100, 72, 5),            # one ragged block of experts, ragged tokens and slab
+    ("bf16", 517, 520, 24),
+    ("bf16", 96, 256, 130),          # two blocks per wave
+    ("bf16", 70, 128, 384),          # three
+    ("bf16", 40, 64, 512),           # four
+    ("bf16", 33, 8, 1000),           # eight, a single 16-byte chunk per row
+    ("bf16", 33000, 64, 128),        # workgroups to spare: two token fragments each
+    ("f32", 50, 100, 12)])
+def test_router_logits_parity(torch_cuda, dtype, T, H, E):
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], dtype=dtype, T=T, H=H, E=E)
+    x, W = synth.activations(cfg), synth.gate_weights(cfg)
+    got = _np(binding.router_logits(binding.to_device(x, dtype), binding.to_device(W, dtype)))
+    want = oracle.router_logits(x, W)
+    assert got.shape == want.shape == (T, E)
+    err = np.abs(got.astype(np.float64) - want).max()
+    print(f"  gate {dtype} T={T} H={H} E={E}: max|ref|={np.abs(want).max():.3g} max|err|={err:.3g}", flush=True)
+    assert err <= GATE_TOL * np.abs(want).max()
+    # sums of a single term are exact: a gate of unit rows copies columns of x
+    U = np.zeros((E, H), dtype=np.float32)
+    U[np.arange(E), np.arange(E) % H] = 1.0
+    got = _np(binding.router_logits(binding.to_device(x, dtype), binding.to_device(U, dtype)))
+    assert np.array_equal(got, x[:, np.arange(E) % H])
+
+
+def test_router_logits_empty_and_rejected(torch_cuda):
+    torch = torch_cuda
+    x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda:0")
+    W = torch.zeros((8, 64), dtype=torch.bfloat16, device="cuda:0")
+    assert tuple(binding.router_logits(x, W).shape) == (0, 8)
+    with pytest.raises(binding.CraftError):                       # bf16 rows must be whole 16-byte chunks
+        binding.router_logits(torch.zeros((4, 12), dtype=torch.bfloat16, device="cuda:0"),
+                              torch.zeros((8, 12), dtype=torch.bfloat16, device="cuda:0"))
+    with pytest.raises(binding.CraftError):                       # more experts than the router takes
+        binding.router_logits(torch.zeros((4, 8), dtype=torch.bfloat16, device="cuda:0"),
+                              torch.zeros((1025, 8), dtype=torch.bfloat16, device="cuda:0"))
+
+
+@pytest.mark.parametrize("name", ["qwen3", "kimi"])
+def test_router_logits_full_size_feeds_the_router(torch_cuda, name):
+    # full shapes; the checker affords a sample of the tokens.  The top-k decision is taken by
+    # both sides on the same fp32 scores (the library's): ids bit-exact.
+    torch = torch_cuda
+    cfg = synth.CONFIGS[name]
+    x, W = synth.activations(cfg), synth.gate_weights(cfg)
+    logits = binding.router_logits(binding.to_device(x, cfg.dtype), binding.to_device(W, cfg.dtype))
+    toks = np.random.default_rng(5).choice(cfg.T, size=192, replace=False)
+    toks = np.concatenate([toks, [0, cfg.T - 1]])
+    want = oracle.router_logits(x[toks], W)
+    got = _np(logits)
+    err = np.abs(got[toks].astype(np.float64) - want).max()
+    print(f"  gate {name}: max|ref|={np.abs(want).max():.3g} max|err|={err:.3g}", flush=True)
+    assert err <= GATE_TOL * np.abs(want).max()
+    ids, w = binding.route_topk(logits, cfg.k)
+    ref_ids, ref_w = oracle.route(got, cfg.k)
+    assert np.array_equal(_np(ids), ref_ids)
+    assert np.allclose(_np(w), ref_w, rtol=1e-5, atol=1e-30)
+
+
 # --------------------------------------------------------------------- forward
 
 def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False, knobs=None):
