@@ -10,21 +10,22 @@
 namespace craft {
 namespace {
 
+// A 16-byte piece of a row as it is loaded, and how it unpacks to fp32 / packs from it.
 template <typename T> struct Chunk;
 template <> struct Chunk<float> {
     static constexpr int N = 4;
-    __device__ static void load(const float *p, float (&v)[4]) {
-        const float4 q = *reinterpret_cast<const float4 *>(p);
-        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    __device__ static void unpack(const uint4 &q, float (&v)[4]) {
+        v[0] = __uint_as_float(q.x); v[1] = __uint_as_float(q.y);
+        v[2] = __uint_as_float(q.z); v[3] = __uint_as_float(q.w);
     }
-    __device__ static void store(float *p, const float (&v)[4]) {
-        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    __device__ static uint4 pack(const float (&v)[4]) {
+        return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]),
+                          __float_as_uint(v[3]));
     }
 };
 template <> struct Chunk<__hip_bfloat16> {
     static constexpr int N = 8;
-    __device__ static void load(const __hip_bfloat16 *p, float (&v)[8]) {
-        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+    __device__ static void unpack(const uint4 &q, float (&v)[8]) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -36,13 +37,13 @@ template <> struct Chunk<__hip_bfloat16> {
         const uint32_t u = __float_as_uint(f);
         return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
     }
-    __device__ static void store(__hip_bfloat16 *p, const float (&v)[8]) {
+    __device__ static uint4 pack(const float (&v)[8]) {
         uint4 q;
         q.x = rne(v[0]) | (rne(v[1]) << 16);
         q.y = rne(v[2]) | (rne(v[3]) << 16);
         q.z = rne(v[4]) | (rne(v[5]) << 16);
         q.w = rne(v[6]) | (rne(v[7]) << 16);
-        *reinterpret_cast<uint4 *>(p) = q;
+        return q;
     }
 };
 
@@ -65,10 +66,11 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
     const T *y = static_cast<const T *>(a.y);
     T *out = static_cast<T *>(a.out) + t * a.H;
     // The chunk loop is uniform over the wave (shuffles need every lane); a lane past the end
-    // of the row only skips its loads and its store.  Four chunks per lane are requested
-    // together, so a wave has four independent loads in flight per assignment instead of a
-    // chain of dependent ones.
-    constexpr int U = 4;
+    // of the row only skips its loads and its store.  A lane owns U chunks of the row and the
+    // rows of up to G assignments are requested together before any of them is added (in
+    // ascending j, as always): what a wave takes is a chain of memory latencies, one per round
+    // of requests, and a token of the busiest rank has several of its experts there.
+    constexpr int U = 8, G = 4;
     for (int base = 0; base < a.H; base += 64 * N * U) {
         int c0[U];
         bool inside[U];
@@ -82,27 +84,45 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
         }
         unsigned long long m = live;
         while (m) {
-            const int j = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const int32_t dj = __shfl(d, j, 64);
-            const float wv = __shfl(wj, j, 64);
-            const T *row = y + (int64_t)(dj - lo) * a.H;
-            float v[U][N];
+            const T *row[G];
+            float wv[G];
+            int n = 0;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (inside[u]) Chunk<T>::load(row + c0[u], v[u]);
-                else
-#pragma unroll
-                    for (int i = 0; i < N; ++i) v[u][i] = 0.0f;
+            for (int g = 0; g < G; ++g) {
+                row[g] = y;
+                wv[g] = 0.0f;
+                if (m) {
+                    const int j = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    row[g] = y + (int64_t)(__shfl(d, j, 64) - lo) * a.H;
+                    wv[g] = __shfl(wj, j, 64);
+                    n = g + 1;
+                }
             }
+            uint4 raw[G][U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int g = 0; g < G; ++g)
+                if (g < n) {
 #pragma unroll
-                for (int i = 0; i < N; ++i) acc[u][i] += wv * v[u][i];
+                    for (int u = 0; u < U; ++u)
+                        raw[g][u] = inside[u] ? *reinterpret_cast<const uint4 *>(row[g] + c0[u])
+                                              : make_uint4(0, 0, 0, 0);
+                }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (g < n) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        float v[N];
+                        Chunk<T>::unpack(raw[g][u], v);
+#pragma unroll
+                        for (int i = 0; i < N; ++i) acc[u][i] += wv[g] * v[i];
+                    }
+                }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (inside[u]) Chunk<T>::store(out + c0[u], acc[u]);
+            if (inside[u]) *reinterpret_cast<uint4 *>(out + c0[u]) = Chunk<T>::pack(acc[u]);
     }
 }
 
