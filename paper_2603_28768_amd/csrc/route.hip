@@ -9,7 +9,7 @@
 // ascending expert order, then a four-step butterfly over the row.  Scores are compared
 // raw, never their exponentials, and equal scores resolve to the lower expert id.
 //
-// A workgroup covers 32 consecutive tokens (two passes of 16).  While the picks are still in
+// A workgroup of eight waves covers 32 consecutive tokens.  While the picks are still in
 // registers it also records, per expert, a 32-bit mask of the block's tokens that chose it:
 // the number of set bits below a token's own bit is that assignment's rank among the
 // block's assignments to the expert (experts of one token are distinct), and the
@@ -19,7 +19,7 @@
 namespace craft {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = 16 * kTokPerBlock;   // a 16-lane row per token of the block
 constexpr int kMaxE = 1024;
 constexpr int kMaxPickSlots = 4;     // k <= 64 picks, 16 lanes per token
 
@@ -68,13 +68,12 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
         __syncthreads();
     }
 
-    int my_id[2][kMaxPickSlots];
+    int my_id[kMaxPickSlots];
+    const int tl = tid >> 4;                       // token inside the block
+    const int64_t t = (int64_t)blockIdx.x * kTokPerBlock + tl;
+    {
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-#pragma unroll
-        for (int s = 0; s < kMaxPickSlots; ++s) my_id[pass][s] = -1;
-        const int tl = pass * 16 + (tid >> 4);     // token inside the block
-        const int64_t t = (int64_t)blockIdx.x * kTokPerBlock + tl;
+        for (int s = 0; s < kMaxPickSlots; ++s) my_id[s] = -1;
         const bool live = t < a.T;                 // uniform over the row
         const float *row = a.logits + (live ? t : 0) * a.E;
 
@@ -124,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
                 argmax_step<kMirror>(bv, bi);
                 // the owner retires the pick; lane j of the row keeps it for the output
                 if (((bi >> 2) & 15) == sub) avail &= ~(1ull << ((bi >> 6) * 4 + (bi & 3)));
-                if (j == sub) { pick_v[s] = bv; my_id[pass][s] = bi; }
+                if (j == sub) { pick_v[s] = bv; my_id[s] = bi; }
                 if (s == 0 && j == 0) first_v = bv;       // the row maximum
             }
         }
@@ -149,28 +148,23 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
             for (int s = 0; s < kMaxPickSlots; ++s) {
                 const int j = s * 16 + sub;
                 if (j < a.k) {
-                    a.ids[t * a.k + j] = my_id[pass][s];
+                    a.ids[t * a.k + j] = my_id[s];
                     a.w[t * a.k + j] = ex[s] / den;
-                    if (ranks) atomicOr(&mask[my_id[pass][s]], 1u << tl);
+                    if (ranks) atomicOr(&mask[my_id[s]], 1u << tl);
                 }
             }
         } else {
 #pragma unroll
-            for (int s = 0; s < kMaxPickSlots; ++s) my_id[pass][s] = -1;
+            for (int s = 0; s < kMaxPickSlots; ++s) my_id[s] = -1;
         }
     }
     if (!ranks) return;
     __syncthreads();
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        const int tl = pass * 16 + (tid >> 4);
-        const int64_t t = (int64_t)blockIdx.x * kTokPerBlock + tl;
-#pragma unroll
-        for (int s = 0; s < kMaxPickSlots; ++s) {
-            const int j = s * 16 + sub;
-            if (t < a.T && j < a.k)
-                a.lrank[t * a.k + j] = (uint8_t)__popc(mask[my_id[pass][s]] & ((1u << tl) - 1u));
-        }
+    for (int s = 0; s < kMaxPickSlots; ++s) {
+        const int j = s * 16 + sub;
+        if (t < a.T && j < a.k)
+            a.lrank[t * a.k + j] = (uint8_t)__popc(mask[my_id[s]] & ((1u << tl) - 1u));
     }
     int32_t *hrow = a.hist + (int64_t)blockIdx.x * a.E;
     for (int e = tid; e < a.E; e += kThreads) hrow[e] = __popc(mask[e]);
