@@ -316,6 +316,20 @@ def test_forward_rejects_foreign_tables(torch_cuda):
         fwd(x, logits)
 
 
+def test_rank_with_more_slots_than_the_tile_tables_in_lds(torch_cuda):
+    # above 256 slots on a rank the FFN walks its tile tables in global memory
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=700, H=64, I=64, E=300, k=4, D=1, replica_slots=6,
+                       zipf_s=1.1, profile_batches=2)
+    case = Case(cfg)
+    rows = case.slot_cnt
+    assert len(rows) > 256 and (rows > 64).any() and ((rows > 0) & (rows <= 32)).any()
+    outs = [_check_rank(torch_cuda, case, 0, packed=True, knobs=knobs)[0]
+            for knobs in (dict(riders_gateup=-1, riders_down=-1),
+                          dict(tile_rows_gateup=128, tile_rows_down=128, riders_gateup=1, riders_down=1))]
+    assert np.array_equal(outs[0], outs[1])
+    _check_rank(torch_cuda, case, 0, packed=False)
+
+
 @pytest.mark.parametrize("w8", [False, True])
 @pytest.mark.parametrize("T,H,I,E,k,D,slots,zipf", [
     (240, 128, 192, 32, 4, 1, 0, 1.0),     # fewer busy tiles than units of the two-fragment slots
