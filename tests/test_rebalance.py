@@ -119,8 +119,32 @@ def test_window_accumulated_on_device_and_replan(torch_cuda):
     reuse, nf, nd = po.plan_diff(po.make_plan(case.W.tolist(), cfg.D, None, cfg.replica_slots)["layers"][0],
                                  ref["layers"][0], rank)
     assert d["reuse"].tolist() == reuse and d["n_fetch"] == nf and d["n_drop"] == nd
-    # a forward under the new plan on a post-shift batch
+    # the swap on this rank: slots that keep an expert it already holds take over the resident
+    # buffers, only the rest is fetched (here: packed afresh); then a forward under the new plan
     after = Case(cfg, plan=fresh, pop=pop1)
+    old_slots, new_slots = case.rank_slots(rank), after.rank_slots(rank)
+    (og, ou, od), opacked = fwd._weights, fwd._packed[0]
+    wg, wu, wd, pk, fetched = [], [], [], [], 0
+    for j, e in enumerate(new_slots):
+        r = int(d["reuse"][j])
+        if r >= 0:
+            assert old_slots[r] == e
+            g_, u_, d_, p_ = og[r], ou[r], od[r], opacked[r]
+        else:
+            fetched += 1
+            g_, u_, d_ = (binding.to_device(m, cfg.dtype) for m in synth.expert_weights(cfg, e))
+            p_ = binding.pack_weights(g_, u_, d_)
+        wg.append(g_); wu.append(u_); wd.append(d_); pk.append(p_)
+    assert fetched == d["n_fetch"]
+    assert sorted(r for r in d["reuse"].tolist() if r >= 0) == sorted(set(r for r in d["reuse"].tolist() if r >= 0))
+    swapped = binding.RankForward(fresh, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k, wg, wu, wd,
+                                  want_debug_outputs=True, packed=pk)
+    xs = binding.to_device(after.x, cfg.dtype)
+    out = swapped(xs, torch.from_numpy(after.logits).to("cuda:0")).float().cpu().numpy().astype(np.float64)
+    r = after.oracle_rank(rank)
+    assert swapped.result() == (r["rows"], 0)
+    assert np.abs(out - r["out"]).max() <= 1e-2 * np.abs(r["out"]).max()
+    # and on the rank that is now the heaviest, with all weights placed afresh
     f2, x2, l2 = after.gpu_rank(after.heaviest, packed=True)
     out = f2(x2, l2).float().cpu().numpy().astype(np.float64)
     rows, ovf = f2.result()
