@@ -14,6 +14,7 @@ namespace {
 
 constexpr int kScanThreads = 1024;
 constexpr int kScanWaves = kScanThreads / 64;
+static_assert(kScanChunk % kScanWaves == 0, "a chunk is dealt to the waves in equal parts");
 
 // Exclusive scan over the workgroup of one value per thread (wave shuffles, then one LDS
 // exchange between the 16 waves).  Returns the exclusive prefix; *total gets the sum.
@@ -40,11 +41,14 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum
     return before + inc - v;
 }
 
-// One workgroup per 64 experts (or a single workgroup for all of them when there are few
-// token blocks).  Wave w owns a contiguous range of blocks; a lane owns one expert.  Each
-// wave sums its range, the waves' sums are prefix-combined through LDS, and the per-block
-// counts are rewritten as exclusive prefixes.  The workgroup that finishes last (ticket
-// counter; trivially the only one) derives everything that needs all counts: rows per slot,
+// Blocks of tokens are taken in chunks of kScanChunk; a workgroup handles one chunk for 64
+// experts (a single workgroup walks over all experts when there is only one chunk).  Wave w
+// owns 16 consecutive blocks of the chunk and a lane owns one expert: each wave sums its
+// blocks (kept in registers), the waves' sums are prefix-combined through LDS, and the
+// per-block counts are rewritten as exclusive prefixes inside the chunk.  With several
+// chunks the chunk totals go to memory and the workgroup that finishes last (ticket
+// counter) turns them into per-chunk bases, which the dispatch kernel adds.  That workgroup
+// (trivially the only one) also derives everything that needs all counts: rows per slot,
 // slot offsets, the rank's row count and the row-tile tables of the grouped GEMMs.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     __shared__ int32_t part[kScanWaves][64];
@@ -52,28 +56,22 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     __shared__ int32_t cnt_lds[1024];
     __shared__ int32_t last_flag;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int rows_per_wave = (a.NB + kScanWaves - 1) / kScanWaves;
-    const int b0 = min(a.NB, wave * rows_per_wave), b1 = min(a.NB, b0 + rows_per_wave);
-    // Launched as one workgroup (few blocks of tokens), it walks over the groups of 64 experts
-    // itself and goes straight on to the tail: no ticket, no device-wide fences.
+    constexpr int kKeep = kScanChunk / kScanWaves;         // blocks per wave
     const bool single = gridDim.x == 1;
     const int groups = (a.E + 63) / 64;
+    const int chunk = single ? 0 : (int)blockIdx.x / groups;
+    const int cb1 = min(a.NB, (chunk + 1) * kScanChunk);
+    const int b0 = min(cb1, chunk * kScanChunk + wave * kKeep), b1 = min(cb1, b0 + kKeep);
 
-    for (int grp = single ? 0 : (int)blockIdx.x; grp < (single ? groups : (int)blockIdx.x + 1); ++grp) {
+    for (int grp = single ? 0 : (int)blockIdx.x % groups; grp < (single ? groups : (int)blockIdx.x % groups + 1); ++grp) {
         const int e = grp * 64 + lane;
-        // the common case keeps a wave's block counts in registers between the two passes
-        constexpr int kKeep = 16;
         int32_t keep[kKeep];
         int32_t sum = 0;
         if (e < a.E) {
-            if (rows_per_wave <= kKeep) {
 #pragma unroll
-                for (int i = 0; i < kKeep; ++i) {
-                    keep[i] = b0 + i < b1 ? a.hist[(int64_t)(b0 + i) * a.E + e] : 0;
-                    sum += keep[i];
-                }
-            } else {
-                for (int b = b0; b < b1; ++b) sum += a.hist[(int64_t)b * a.E + e];
+            for (int i = 0; i < kKeep; ++i) {
+                keep[i] = b0 + i < b1 ? a.hist[(int64_t)(b0 + i) * a.E + e] : 0;
+                sum += keep[i];
             }
         }
         part[wave][lane] = sum;
@@ -87,22 +85,17 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         }
         if (e < a.E) {
             int32_t run = before;
-            if (rows_per_wave <= kKeep) {
 #pragma unroll
-                for (int i = 0; i < kKeep; ++i)
-                    if (b0 + i < b1) { a.hist[(int64_t)(b0 + i) * a.E + e] = run; run += keep[i]; }
-            } else {
-                for (int b = b0; b < b1; ++b) {
-                    int32_t *p = a.hist + (int64_t)b * a.E + e;
-                    const int32_t v = *p;
-                    *p = run;
-                    run += v;
-                }
-            }
+            for (int i = 0; i < kKeep; ++i)
+                if (b0 + i < b1) { a.hist[(int64_t)(b0 + i) * a.E + e] = run; run += keep[i]; }
             if (wave == 0) {
-                a.counts[e] = total;
-                if (a.user_counts) a.user_counts[e] = total;
-                if (single) cnt_lds[e] = total;
+                if (single) {
+                    a.counts[e] = total;
+                    if (a.user_counts) a.user_counts[e] = total;
+                    cnt_lds[e] = total;
+                } else {
+                    a.chunk_tot[(int64_t)chunk * a.E + e] = total;
+                }
             }
         }
         __syncthreads();                   // `part` is reused by the next group
@@ -119,16 +112,26 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         __syncthreads();
         if (!last_flag) return;
         __threadfence();
+        // chunk totals -> chunk bases and the experts' counts
+        const int chunks = (int)gridDim.x / groups;
+        for (int32_t e = threadIdx.x; e < a.E; e += kScanThreads) {
+            int32_t run = 0;
+            for (int c = 0; c < chunks; ++c) {
+                a.chunk_base[(int64_t)c * a.E + e] = run;
+                run += __hip_atomic_load(a.chunk_tot + (int64_t)c * a.E + e, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            }
+            a.counts[e] = run;
+            if (a.user_counts) a.user_counts[e] = run;
+            cnt_lds[e] = run;
+        }
     }
+    __syncthreads();
 
     const craft_tables_header *hdr = reinterpret_cast<const craft_tables_header *>(a.tables);
     const int32_t *copies = a.tables + hdr->off_copies;
     const int32_t *slot_expert = a.tables + hdr->off_slot_expert;
     const int32_t *slot_copy = a.tables + hdr->off_slot_copy;
-    if (!single)
-        for (int32_t i = threadIdx.x; i < a.E; i += kScanThreads)
-            cnt_lds[i] = __hip_atomic_load(a.counts + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
 
     // rows of slot p: tokens i < n of its expert with i mod c == q.  Slots are taken in
     // chunks of one per thread; `carry` is the running offset across chunks.
@@ -245,11 +248,13 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a) {
     const int64_t A = a.T * a.k;
     const int32_t per_block = kTokPerBlock * a.k;
     const int32_t *base = a.base + (int64_t)blockIdx.x * a.E;
+    // several chunks of blocks: the prefixes are chunk-local, the chunk's base comes on top
+    const int32_t *cbase = a.chunk_base ? a.chunk_base + (int64_t)(blockIdx.x / kScanChunk) * a.E : nullptr;
     for (int32_t i = threadIdx.x; i < per_block; i += blockDim.x) {
         const int64_t as = (int64_t)blockIdx.x * per_block + i;
         if (as >= A) break;
         const int32_t e = a.ids[as];
-        const int32_t idx = base[e] + (int32_t)a.lrank[as];    // i-th assignment of expert e
+        const int32_t idx = base[e] + (cbase ? cbase[e] : 0) + (int32_t)a.lrank[as];   // i-th assignment of expert e
         const int32_t c = copies[e];
         const int32_t q = idx % c;
         const int32_t p = eslots[efirst[e] + q];
@@ -264,8 +269,9 @@ __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a) {
 }  // namespace
 
 hipError_t launch_scan(const ScanArgs &a, hipStream_t s) {
-    // few token blocks: one workgroup does everything; many: one workgroup per 64 experts
-    const unsigned blocks = a.NB <= 16 * kScanWaves ? 1u : (unsigned)((a.E + 63) / 64);
+    // one chunk of token blocks: one workgroup does everything; more: one per chunk and 64 experts
+    const unsigned chunks = (unsigned)((a.NB + kScanChunk - 1) / kScanChunk);
+    const unsigned blocks = chunks <= 1 ? 1u : chunks * (unsigned)((a.E + 63) / 64);
     hipLaunchKernelGGL(scan_kernel, dim3(blocks), dim3(kScanThreads), 0, s, a);
     return hipGetLastError();
 }

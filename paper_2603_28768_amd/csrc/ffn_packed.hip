@@ -1,4 +1,5 @@
-// Grouped SwiGLU expert FFN over pre-packed bf16 weights: the weight-streaming kernels.
+// Grouped SwiGLU expert FFN over pre-packed weights (bf16, or E4M3 codes with a scale per
+// row): the weight-streaming kernels.
 //
 // Under skewed routing a rank's slots split into a few with hundreds of rows and many with
 // a handful, so the two grouped GEMMs of the expert FFN (Sec. 2.1) are partly matrix-bound
@@ -20,18 +21,24 @@
 //     lane).  The large tile is what keeps the L2-to-CU traffic per flop low enough: a
 //     weight fragment loaded into a CU is used against 256 rows, an activation fragment
 //     against 128 (gate/up) or 256 (down) output columns.
-//   * The weight stream runs 4 to 16 steps ahead of the MFMAs in a statically indexed
-//     register ring (deeper for tiles with few rows); the activation rows (gathered through the dispatch permutation
-//     for gate/up) are shared by the four waves through LDS, double buffered, staged through
-//     registers two slabs ahead.  The contraction loop has no branch around a memory
-//     operation, so the in-order load counter lets all of that stay in flight.
+//   * The weight stream runs 8 or 16 steps ahead of the MFMAs in a statically indexed
+//     register ring (deeper for tiles with few rows); the activation rows (gathered through
+//     the dispatch permutation for gate/up) are shared by the four waves through LDS (three
+//     stages, one barrier per 64-wide slab), staged through registers a slab ahead.  The
+//     contraction loop has no branch around a memory operation, so the in-order load counter
+//     lets all of that stay in flight.
+//   * Under full load a CU gets about 45 GB/s out of L2 whatever it asks for, and a step moves
+//     8 KB of weights plus 1 KB per row fragment into it: at 256 x 256 the tile needs those
+//     bytes about as fast as the MFMAs consume them, below that it is bound by them.  Only
+//     fewer bytes per flop make it faster (8-bit weights); deeper rings do not.
 //   * Row fragments beyond a tile's valid rows are skipped entirely (loads, LDS traffic,
 //     MFMAs): a slot with 20 rows costs one eighth of the matrix work of a full tile while
 //     streaming the same weights.
 //   * Tiles are listed busiest slot first.  Each workgroup takes one tile by position (the
 //     XCD-aware mapping of ffn_common.h, so tiles sharing weights start together on one
 //     XCD), then pulls further tiles from an atomic counter: the cheap streaming tiles of
-//     the cold slots fill in behind the matrix-bound ones.
+//     the cold slots fill in behind the matrix-bound ones, or ride along with them (see
+//     kRiderHostFrags in kernels.h).
 #include "ffn_common.h"
 
 namespace craft {

@@ -20,7 +20,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- workspace layout of one forward -------------------------------------------------
 struct Layout {
-    size_t ctrl, ids, w, lrank, dest, src, hist, counts, slot_cnt, slot_off, mt_start, order, act, y, total;
+    size_t ctrl, ids, w, lrank, dest, src, hist, chunk_tot, chunk_base, counts, slot_cnt, slot_off, mt_start, order, act, y, total;
     int64_t max_rows, NB;
 };
 
@@ -41,6 +41,9 @@ Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, i
     L.dest = take((size_t)A * 4);
     L.src = take((size_t)A * 4);
     L.hist = take((size_t)L.NB * E * 4);
+    const size_t chunks = (size_t)(L.NB + kScanChunk - 1) / kScanChunk;
+    L.chunk_tot = take(chunks * E * 4);
+    L.chunk_base = take(chunks * E * 4);
     L.counts = take((size_t)E * 4);
     L.slot_cnt = take((size_t)S * 4);
     L.slot_off = take((size_t)(S + 1) * 4);
@@ -405,6 +408,9 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     int32_t *dest = reinterpret_cast<int32_t *>(ws + L.dest);
     int32_t *src = reinterpret_cast<int32_t *>(ws + L.src);
     int32_t *hist = reinterpret_cast<int32_t *>(ws + L.hist);
+    int32_t *chunk_tot = reinterpret_cast<int32_t *>(ws + L.chunk_tot);
+    int32_t *chunk_base = reinterpret_cast<int32_t *>(ws + L.chunk_base);
+    const bool chunked = L.NB > kScanChunk;
     int32_t *counts = reinterpret_cast<int32_t *>(ws + L.counts);
     int32_t *slot_cnt = reinterpret_cast<int32_t *>(ws + L.slot_cnt);
     int32_t *slot_off = reinterpret_cast<int32_t *>(ws + L.slot_off);
@@ -426,7 +432,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 2 per-expert totals, slot offsets, tile table
     {
         ScopedEvent ev(CRAFT_K_SCAN, s);
-        ScanArgs sa{hist, (int32_t)L.NB, E, tables, S, s_lo, s_hi, tiles.frags[0], tiles.frags[1], L.max_rows,
+        ScanArgs sa{hist, chunk_tot, chunk_base, (int32_t)L.NB, E, tables, S, s_lo, s_hi, tiles.frags[0], tiles.frags[1], L.max_rows,
                     counts, slot_cnt, slot_off, mt_start, order, tiles.riders[0] ? (a->I + 127) / 128 : 0,
                     tiles.riders[1] ? (a->H + 255) / 256 : 0, ctrl,
                     a->counts, a->slot_cnt, a->slot_off};
@@ -435,7 +441,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     // 3 dispatch permutation
     {
         ScopedEvent ev(CRAFT_K_DISPATCH, s);
-        DispatchArgs da{ids_out, lrank, hist, a->T, a->k, E, tables, slot_off, dest, src, a->dest, a->src};
+        DispatchArgs da{ids_out, lrank, hist, chunked ? chunk_base : nullptr, a->T, a->k, E, tables, slot_off, dest, src, a->dest, a->src};
         if (launch_dispatch(da, s) != hipSuccess) return CRAFT_EHIP;
     }
     // 4 grouped FFN

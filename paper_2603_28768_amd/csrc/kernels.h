@@ -13,6 +13,8 @@ namespace craft {
 // Tokens handled by one workgroup of the routing and dispatch kernels.  Ranks of
 // assignments inside a block are taken from a 32-bit token mask per expert.
 constexpr int kTokPerBlock = 32;
+// Blocks of tokens whose per-expert counts one workgroup of the scan kernel prefixes.
+constexpr int kScanChunk = 256;
 
 // Control words at the start of the workspace.
 enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
@@ -72,7 +74,9 @@ struct RouteArgs {
 hipError_t launch_route(const RouteArgs &a, hipStream_t s);
 
 struct ScanArgs {
-    int32_t *hist;            // [NB][E] in: counts per block; out: exclusive prefix over blocks
+    int32_t *hist;            // [NB][E] in: counts per block; out: exclusive prefix over the blocks of a chunk
+    int32_t *chunk_tot;       // [chunks][E] totals of the chunks (scratch; more than one chunk only)
+    int32_t *chunk_base;      // [chunks][E] out: sum of the earlier chunks' totals
     int32_t NB, E;
     const int32_t *tables;    // device tables of this (layer, rank)
     int32_t S, s_lo, s_hi;
@@ -93,7 +97,8 @@ hipError_t launch_scan(const ScanArgs &a, hipStream_t s);
 struct DispatchArgs {
     const int32_t *ids;
     const uint8_t *lrank;
-    const int32_t *base;      // [NB][E]
+    const int32_t *base;      // [NB][E] prefixes inside a chunk of blocks
+    const int32_t *chunk_base; // [chunks][E] on top of them; null when there is one chunk
     int64_t T;
     int32_t k, E;
     const int32_t *tables;
