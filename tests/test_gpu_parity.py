@@ -230,6 +230,48 @@ def test_forward_is_reproducible_bit_for_bit(torch_cuda):
             assert torch.equal(da[k], v), k
 
 
+def test_forward_replays_from_a_hip_graph(torch_cuda):
+    # the forward is launches only (counters are cleared by a kernel, not a memset node), so it
+    # can be captured; every replay, with eager work and synchronisations in between, has to
+    # give the bits of the eager forward on the same inputs
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=700, H=256, I=256, E=32, D=4, replica_slots=4,
+                       profile_batches=2)
+    case = Case(cfg)
+    fwd, x, logits = case.gpu_rank(case.heaviest, packed=True)
+    sx, sl = x.clone(), logits.clone()                 # the captured launches read these buffers
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            fwd(sx, sl)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fwd(sx, sl)
+    torch.cuda.synchronize()
+    for shift in (0, 1, 37, 350):
+        xs, ls = torch.roll(x, shift, 0), torch.roll(logits, shift, 0)   # other tokens, other routing
+        want = fwd(xs, ls).clone()
+        want_dest = fwd.debug["dest"].clone()
+        torch.cuda.synchronize()
+        sx.copy_(xs)
+        sl.copy_(ls)
+        fwd.out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(fwd.out, want), shift
+        assert torch.equal(fwd.debug["dest"], want_dest), shift
+    ref = case.oracle_rank(case.heaviest)
+    sx.copy_(x)
+    sl.copy_(logits)
+    graph.replay()
+    torch.cuda.synchronize()
+    out = fwd.out.float().cpu().numpy().astype(np.float64)
+    assert np.abs(out - ref["out"]).max() <= TOL[cfg.dtype] * np.abs(ref["out"]).max()
+
+
 def test_rank_without_rows_and_unused_experts(torch_cuda):
     # strong skew on few tokens: some experts (and with D = E some ranks) get nothing
     cfg = synth.scaled(synth.CONFIGS["qwen3"], T=24, H=128, I=64, E=16, k=2, D=16,
