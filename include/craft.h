@@ -53,11 +53,22 @@ enum { CRAFT_F32 = 0, CRAFT_BF16 = 1 };
  *   w_router  DEVICE [E][H], 16-byte aligned
  *   logits    DEVICE [T][E] fp32, fully overwritten; what craft_route_topk and
  *             craft_moe_rank_forward take as their scores
+ *   workspace DEVICE, 16-byte aligned, optional: with at least
+ *             craft_router_logits_workspace() bytes the contraction is split over several
+ *             workgroups per tile of tokens (partial scores in the workspace, added in a
+ *             fixed order by a second kernel), which is what keeps every CU busy at these
+ *             shapes; NULL or too small: one workgroup per tile does the whole sum.  Either
+ *             way the result depends on the arguments only, never on scheduling; the two
+ *             ways round differently.  Calls that share a workspace must be ordered on
+ *             one stream.
  * Limits: 1 <= E <= 1024, H >= 1, H % 8 == 0 for bf16.  T may be 0.  Asynchronous on
  * `stream`; CRAFT_EINVAL on a bad size, a NULL or a misaligned pointer.
  */
+craft_status craft_router_logits_workspace(int32_t dtype, int64_t T, int32_t H, int32_t E,
+                                           size_t *bytes);
 craft_status craft_router_logits(int32_t dtype, const void *x, const void *w_router, int64_t T,
-                                 int32_t H, int32_t E, float *logits, void *stream);
+                                 int32_t H, int32_t E, float *logits, void *workspace,
+                                 size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ routing
  * Sec. 2.1: the gating network's scores select the top-K experts of each token.

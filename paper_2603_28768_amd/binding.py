@@ -44,7 +44,8 @@ class FwdArgs(ctypes.Structure):
 
 EXPORTS = {
     "craft_status_str": (ctypes.c_char_p, [ctypes.c_int]),
-    "craft_router_logits": (ctypes.c_int, [c_i32, c_vp, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
+    "craft_router_logits_workspace": (ctypes.c_int, [c_i32, c_i64, c_i32, c_i32, P(c_sz)]),
+    "craft_router_logits": (ctypes.c_int, [c_i32, c_vp, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp, c_sz, c_vp]),
     "craft_route_topk": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp]),
     "craft_expert_load": (ctypes.c_int, [c_vp, c_i32, c_i64, c_i32, c_i32, c_i64, c_vp, c_vp]),
     "craft_load_accumulate": (ctypes.c_int, [c_vp, c_i64, c_vp, c_vp]),
@@ -123,8 +124,20 @@ def _dev(t):
 
 # ------------------------------------------------------------------------ routing
 
-def router_logits(x, w_router, stream=None):
-    """x: cuda [T][H], w_router: cuda [E][H] (both float32 or both bfloat16) -> float32 [T][E]."""
+def router_logits_workspace(x, w_router):
+    """A workspace tensor of the size craft_router_logits splits its contraction with, or None
+    when this shape is not split."""
+    import torch
+    T, H = x.shape
+    n = c_sz()
+    _check(lib().craft_router_logits_workspace(CRAFT_BF16 if x.dtype == torch.bfloat16 else CRAFT_F32,
+                                               T, H, w_router.shape[0], n), "craft_router_logits_workspace")
+    return torch.empty(n.value, dtype=torch.uint8, device=x.device) if n.value else None
+
+
+def router_logits(x, w_router, workspace=None, stream=None):
+    """x: cuda [T][H], w_router: cuda [E][H] (both float32 or both bfloat16) -> float32 [T][E].
+    `workspace`: a tensor from router_logits_workspace (the faster, split form) or None."""
     import torch
     assert x.dim() == 2 and w_router.dim() == 2 and x.shape[1] == w_router.shape[1]
     assert x.dtype == w_router.dtype and x.dtype in (torch.float32, torch.bfloat16)
@@ -133,7 +146,10 @@ def router_logits(x, w_router, stream=None):
     E = w_router.shape[0]
     logits = torch.empty((T, E), dtype=torch.float32, device=x.device)
     _check(lib().craft_router_logits(CRAFT_BF16 if x.dtype == torch.bfloat16 else CRAFT_F32, _dev(x),
-                                     _dev(w_router), T, H, E, _dev(logits), _stream_ptr(stream)),
+                                     _dev(w_router), T, H, E, _dev(logits),
+                                     _dev(workspace) if workspace is not None else None,
+                                     workspace.numel() if workspace is not None else 0,
+                                     _stream_ptr(stream)),
            "craft_router_logits")
     return logits
 

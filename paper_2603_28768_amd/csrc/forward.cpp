@@ -239,15 +239,32 @@ craft_status check_fwd(const craft_plan_t *plan, int32_t layer, int32_t rank, co
 
 extern "C" {
 
+craft_status craft_router_logits_workspace(int32_t dtype, int64_t T, int32_t H, int32_t E,
+                                           size_t *bytes) {
+    if (!bytes || (dtype != CRAFT_F32 && dtype != CRAFT_BF16)) return CRAFT_EINVAL;
+    if (T < 0 || H <= 0 || E <= 0 || E > 1024 || (dtype == CRAFT_BF16 && H % 8)) return CRAFT_EINVAL;
+    int nxf = 1, nsplit = 1;
+    if (dtype == CRAFT_BF16 && T > 0) router_logits_shape(T, H, E, cached_num_cu(), true, &nxf, &nsplit);
+    *bytes = nsplit > 1 ? (size_t)nsplit * (size_t)T * (size_t)E * sizeof(float) : 0;
+    return CRAFT_OK;
+}
+
 craft_status craft_router_logits(int32_t dtype, const void *x, const void *w_router, int64_t T,
-                                 int32_t H, int32_t E, float *logits, void *stream) {
+                                 int32_t H, int32_t E, float *logits, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
     if (dtype != CRAFT_F32 && dtype != CRAFT_BF16) return CRAFT_EINVAL;
     if (T < 0 || H <= 0 || E <= 0 || E > 1024 || (dtype == CRAFT_BF16 && H % 8)) return CRAFT_EINVAL;
     if (T * (int64_t)E >= ((int64_t)1 << 40)) return CRAFT_EINVAL;
     if (T == 0) return CRAFT_OK;
     if (!x || !w_router || !logits || !aligned(x, 16) || !aligned(w_router, 16) || !aligned(logits, 4))
         return CRAFT_EINVAL;
-    RouterArgs ra{dtype, x, w_router, T, H, E, logits, cached_num_cu()};
+    if (workspace && !aligned(workspace, 16)) return CRAFT_EINVAL;
+    size_t need = 0;
+    craft_status st = craft_router_logits_workspace(dtype, T, H, E, &need);
+    if (st != CRAFT_OK) return st;
+    const bool split = workspace && need > 0 && workspace_bytes >= need;
+    RouterArgs ra{dtype, x, w_router, T, H, E, logits, cached_num_cu(),
+                  split ? static_cast<float *>(workspace) : nullptr, 1};
     return launch_router_logits(ra, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
 

@@ -58,8 +58,11 @@ struct RouterArgs {
     int32_t H, E;
     float *logits;            // [T][E]
     int32_t num_cu;
+    float *part;              // [nsplit][T][E] partial scores when the contraction is split; may be null
+    int32_t nsplit;           // set by the launcher
 };
 hipError_t launch_router_logits(const RouterArgs &a, hipStream_t s);
+void router_logits_shape(int64_t T, int32_t H, int32_t E, int32_t num_cu, bool workspace, int *nxf, int *nsplit);
 
 struct RouteArgs {
     const float *logits;

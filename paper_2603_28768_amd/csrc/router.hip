@@ -15,11 +15,11 @@
 // experts of one token: stores are 128 contiguous bytes.
 // What bounds it: every workgroup pulls the whole gate out of L2, so T H 2 (1 + E / tokens
 // per workgroup) bytes move from L2 into the CUs, at the 11-12 TB/s the chip sustains there
-// with every CU pulling.  Taller workgroups would move less but leave CUs idle (T / 128
-// workgroups) and serialise LDS traffic and MFMAs inside one wave per SIMD; they measured
-// slower, as did gate rows loaded straight into registers in operand layout (32-byte pieces
-// of 32 rows per request).  Splitting the contraction over workgroups, with partial scores
-// in a workspace and a second pass adding them in a fixed order, is the way past this.
+// with every CU pulling.  Taller workgroups move less but there are only T / 128 of them, so
+// with a workspace the contraction is split over up to 8 workgroups per tile: each writes
+// its partial scores and a second kernel adds them in ascending order of the split (a fixed
+// order: the result does not depend on scheduling).  Gate rows loaded straight into
+// registers in operand layout (32-byte pieces of 32 rows per request) measured slower.
 // fp32: one thread per score, a plain chain of fused multiply-adds (small configurations).
 #include "ffn_common.h"
 
@@ -40,8 +40,13 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(RouterArgs a) {
     const int frag_off = (lane & 31) * GROWB + (lane >> 5) * 16;
     const int64_t t0 = (int64_t)blockIdx.x * (NXF * 32);
     const int e0 = blockIdx.y * (NB * 128);
-    const int nk = (a.H + GK - 1) / GK;
     const int hchunks = a.H >> 3;                          // 16-byte chunks per row
+    // this workgroup's share of the contraction: slabs kbeg .. kbeg + nk - 1 (nk may be 0)
+    const int nk_all = (a.H + GK - 1) / GK;
+    const int per = (nk_all + a.nsplit - 1) / a.nsplit;
+    const int kbeg = min(nk_all, (int)blockIdx.z * per);
+    const int nk = min(nk_all, kbeg + per) - kbeg;
+    float *dst = a.nsplit > 1 ? a.part + (int64_t)blockIdx.z * a.T * a.E : a.logits;
 
     // rows past the end are clamped into the matrix (their results are not stored)
     gchunk_t xrow[NXF], wrow[NB * 4];
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(RouterArgs a) {
     // the same on every path for the waits to let D slabs stay outstanding (past the last
     // slab the last one is requested again and never used)
 #pragma unroll
-    for (int d = 0; d < D; ++d) GATE_REQUEST(d, min(d, nk - 1))
+    for (int d = 0; d < D; ++d) GATE_REQUEST(d, min(kbeg + d, nk_all - 1))
     for (int ks0 = 0; ks0 < nk; ks0 += 2 * D) {
 #pragma unroll
         for (int dd = 0; dd < 2 * D; ++dd) {               // 2 D slabs per trip: set and stage are static
@@ -84,7 +89,7 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(RouterArgs a) {
             const int d = dd % D;
             unsigned char *xs = gate_smem + (dd & 1) * STAGEB;
             unsigned char *ws = xs + NXF * 32 * GROWB;
-            const bool in = ks * (GK / 8) + kc < hchunks;
+            const bool in = (kbeg + ks) * (GK / 8) + kc < hchunks;
 #pragma unroll
             for (int i = 0; i < NXF; ++i)
                 *reinterpret_cast<gu32x4_t *>(xs + (lr + 32 * i) * GROWB + kc * 16) = in ? xr[d][i] : zero;
@@ -94,7 +99,7 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(RouterArgs a) {
             // one barrier per slab: the other stage is rewritten only after every wave has
             // passed this one, that is, has finished reading it
             __syncthreads();
-            GATE_REQUEST(d, min(ks + D, nk - 1))
+            GATE_REQUEST(d, min(kbeg + ks + D, nk_all - 1))
 #pragma unroll
             for (int step = 0; step < GK / 16; ++step) {
                 bf16x8_t xa[NXF];
@@ -124,9 +129,18 @@ __global__ __launch_bounds__(256) void router_logits_bf16_kernel(RouterArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t t = t0 + g * 32 + (v / 4) * 8 + (lane >> 5) * 4 + v % 4;
-                if (t < a.T && e < a.E) a.logits[t * a.E + e] = acc[b][g][v];
+                if (t < a.T && e < a.E) dst[t * a.E + e] = acc[b][g][v];
             }
     }
+}
+
+// logits = sum of the partial scores, in ascending order of the split
+__global__ __launch_bounds__(256) void router_reduce_kernel(const float *part, int nsplit, int64_t n, float *logits) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = part[i];
+    for (int z = 1; z < nsplit; ++z) s += part[(int64_t)z * n + i];
+    logits[i] = s;
 }
 
 __global__ __launch_bounds__(256) void router_logits_f32_kernel(RouterArgs a) {
@@ -150,12 +164,37 @@ hipError_t launch_bf16(const RouterArgs &a, hipStream_t s) {
         if (e != hipSuccess) return e;
         raised = true;
     }
-    const dim3 grid((unsigned)((a.T + NXF * 32 - 1) / (NXF * 32)), (unsigned)((a.E + NB * 128 - 1) / (NB * 128)));
+    const dim3 grid((unsigned)((a.T + NXF * 32 - 1) / (NXF * 32)), (unsigned)((a.E + NB * 128 - 1) / (NB * 128)),
+                    (unsigned)a.nsplit);
     hipLaunchKernelGGL((router_logits_bf16_kernel<NB, NXF, D>), grid, dim3(256), lds, s, a);
+    if (a.nsplit > 1) {
+        const int64_t n = a.T * a.E;
+        hipLaunchKernelGGL(router_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                           a.part, a.nsplit, n, a.logits);
+    }
     return hipGetLastError();
 }
 
 }  // namespace
+
+// Tile height (32-token fragments per workgroup) and split of the contraction for a shape.
+// Without a workspace: short tiles, as many as there are CUs if possible.  With one: the
+// tallest tile the registers allow, and as many splits as bring the workgroups up to the CU
+// count (at most 8, at least 4 slabs each).
+void router_logits_shape(int64_t T, int32_t H, int32_t E, int32_t num_cu, bool workspace, int *nxf, int *nsplit) {
+    const int nb = E > 512 ? 4 : (E + 127) / 128;
+    *nsplit = 1;
+    if (!workspace || nb > 2) {
+        *nxf = nb <= 3 && (T + 63) / 64 >= (int64_t)num_cu ? 2 : 1;
+        return;
+    }
+    *nxf = 4;
+    const int64_t tiles = (T + 127) / 128 * ((E + nb * 128 - 1) / (nb * 128));
+    const int nk = (H + GK - 1) / GK;
+    int sp = 1;
+    while (sp < 8 && tiles * sp * 2 <= num_cu && nk / (sp * 2) >= 4) sp *= 2;
+    *nsplit = sp;
+}
 
 hipError_t launch_router_logits(const RouterArgs &a, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
@@ -165,12 +204,20 @@ hipError_t launch_router_logits(const RouterArgs &a, hipStream_t s) {
         return hipGetLastError();
     }
     const int nb = a.E > 512 ? 4 : (a.E + 127) / 128;      // blocks of 32 experts per wave
-    const bool two = (a.T + 63) / 64 >= (int64_t)a.num_cu;  // two token fragments if every CU still gets work
-    switch (nb) {
-        case 1: return two ? launch_bf16<1, 2, 4>(a, s) : launch_bf16<1, 1, 4>(a, s);
-        case 2: return two ? launch_bf16<2, 2, 4>(a, s) : launch_bf16<2, 1, 4>(a, s);
-        case 3: return two ? launch_bf16<3, 2, 3>(a, s) : launch_bf16<3, 1, 3>(a, s);
-        default: return launch_bf16<4, 1, 3>(a, s);
+    int nxf, nsplit;
+    router_logits_shape(a.T, a.H, a.E, a.num_cu, a.part != nullptr, &nxf, &nsplit);
+    RouterArgs b = a;
+    b.nsplit = nsplit;
+    switch (nb * 16 + nxf) {
+        case 1 * 16 + 1: return launch_bf16<1, 1, 4>(b, s);
+        case 1 * 16 + 2: return launch_bf16<1, 2, 4>(b, s);
+        case 1 * 16 + 4: return launch_bf16<1, 4, 4>(b, s);
+        case 2 * 16 + 1: return launch_bf16<2, 1, 4>(b, s);
+        case 2 * 16 + 2: return launch_bf16<2, 2, 4>(b, s);
+        case 2 * 16 + 4: return launch_bf16<2, 4, 3>(b, s);
+        case 3 * 16 + 1: return launch_bf16<3, 1, 3>(b, s);
+        case 3 * 16 + 2: return launch_bf16<3, 2, 3>(b, s);
+        default: return launch_bf16<4, 1, 3>(b, s);
     }
 }
 

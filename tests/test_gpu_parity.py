@@ -101,21 +101,30 @@ GATE_TOL = 1e-4
     ("bf16", 40, 64, 512),           # four
     ("bf16", 33, 8, 1000),           # eight, a single 16-byte chunk per row
     ("bf16", 33000, 64, 128),        # workgroups to spare: two token fragments each
+    ("bf16", 300, 2048, 200),        # with a workspace: the contraction split eight ways
+    ("bf16", 200, 1000, 100),        # split, ragged last slab and a last split shorter than the rest
     ("f32", 50, 100, 12)])
 def test_router_logits_parity(torch_cuda, dtype, T, H, E):
     cfg = synth.scaled(synth.CONFIGS["qwen3"], dtype=dtype, T=T, H=H, E=E)
     x, W = synth.activations(cfg), synth.gate_weights(cfg)
-    got = _np(binding.router_logits(binding.to_device(x, dtype), binding.to_device(W, dtype)))
+    xd, Wd = binding.to_device(x, dtype), binding.to_device(W, dtype)
     want = oracle.router_logits(x, W)
-    assert got.shape == want.shape == (T, E)
-    err = np.abs(got.astype(np.float64) - want).max()
-    print(f"  gate {dtype} T={T} H={H} E={E}: max|ref|={np.abs(want).max():.3g} max|err|={err:.3g}", flush=True)
-    assert err <= GATE_TOL * np.abs(want).max()
-    # sums of a single term are exact: a gate of unit rows copies columns of x
     U = np.zeros((E, H), dtype=np.float32)
     U[np.arange(E), np.arange(E) % H] = 1.0
-    got = _np(binding.router_logits(binding.to_device(x, dtype), binding.to_device(U, dtype)))
-    assert np.array_equal(got, x[:, np.arange(E) % H])
+    Ud = binding.to_device(U, dtype)
+    ws = binding.router_logits_workspace(xd, Wd)
+    print(f"  gate {dtype} T={T} H={H} E={E}: workspace {0 if ws is None else ws.numel()} bytes", flush=True)
+    for workspace in ([None] if ws is None else [None, ws]):    # one workgroup per tile / split contraction
+        got = _np(binding.router_logits(xd, Wd, workspace))
+        assert got.shape == want.shape == (T, E)
+        err = np.abs(got.astype(np.float64) - want).max()
+        print(f"    max|ref|={np.abs(want).max():.3g} max|err|={err:.3g}", flush=True)
+        assert err <= GATE_TOL * np.abs(want).max()
+        # sums of a single term are exact: a gate of unit rows copies columns of x
+        got = _np(binding.router_logits(xd, Ud, workspace))
+        assert np.array_equal(got, x[:, np.arange(E) % H])
+        # and the result depends on the arguments only
+        assert np.array_equal(_np(binding.router_logits(xd, Wd, workspace)), _np(binding.router_logits(xd, Wd, workspace)))
 
 
 def test_router_logits_empty_and_rejected(torch_cuda):
@@ -138,7 +147,8 @@ def test_router_logits_full_size_feeds_the_router(torch_cuda, name):
     torch = torch_cuda
     cfg = synth.CONFIGS[name]
     x, W = synth.activations(cfg), synth.gate_weights(cfg)
-    logits = binding.router_logits(binding.to_device(x, cfg.dtype), binding.to_device(W, cfg.dtype))
+    xd, Wd = binding.to_device(x, cfg.dtype), binding.to_device(W, cfg.dtype)
+    logits = binding.router_logits(xd, Wd, binding.router_logits_workspace(xd, Wd))
     toks = np.random.default_rng(5).choice(cfg.T, size=192, replace=False)
     toks = np.concatenate([toks, [0, cfg.T - 1]])
     want = oracle.router_logits(x[toks], W)
