@@ -184,7 +184,7 @@ hipError_t launch_bf16(const RouterArgs &a, hipStream_t s) {
 void router_logits_shape(int64_t T, int32_t H, int32_t E, int32_t num_cu, bool workspace, int *nxf, int *nsplit) {
     const int nb = E > 512 ? 4 : (E + 127) / 128;
     *nsplit = 1;
-    if (!workspace || nb > 2) {
+    if (!workspace || nb > 3) {
         *nxf = nb <= 3 && (T + 63) / 64 >= (int64_t)num_cu ? 2 : 1;
         return;
     }
@@ -217,6 +217,7 @@ hipError_t launch_router_logits(const RouterArgs &a, hipStream_t s) {
         case 2 * 16 + 4: return launch_bf16<2, 4, 3>(b, s);
         case 3 * 16 + 1: return launch_bf16<3, 1, 3>(b, s);
         case 3 * 16 + 2: return launch_bf16<3, 2, 3>(b, s);
+        case 3 * 16 + 4: return launch_bf16<3, 4, 1>(b, s);
         default: return launch_bf16<4, 1, 3>(b, s);
     }
 }

@@ -103,6 +103,7 @@ GATE_TOL = 1e-4
     ("bf16", 33000, 64, 128),        # workgroups to spare: two token fragments each
     ("bf16", 300, 2048, 200),        # with a workspace: the contraction split eight ways
     ("bf16", 200, 1000, 100),        # split, ragged last slab and a last split shorter than the rest
+    ("bf16", 200, 1024, 384),        # split with three blocks of experts per wave
     ("f32", 50, 100, 12)])
 def test_router_logits_parity(torch_cuda, dtype, T, H, E):
     cfg = synth.scaled(synth.CONFIGS["qwen3"], dtype=dtype, T=T, H=H, E=E)
