@@ -264,7 +264,9 @@ craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_c
  *                 w[t][j] * Y[row of (t,j)]; tokens with none get zeros
  *
  *   x        DEVICE [T][H] activations, dtype
- *   logits   DEVICE [T][E] fp32
+ *   logits   DEVICE [T][E] fp32 router scores, or NULL: then the forward computes them first,
+ *            as craft_router_logits does (with its workspace), from
+ *   w_router DEVICE [E][H] gate weights, dtype (ignored when logits is given)
  *   w_gate, w_up  DEVICE arrays of s device pointers, one per slot of this rank in slot
  *                 order, each to a [I][H] matrix of dtype
  *   w_down        likewise, each [H][I]
@@ -300,6 +302,7 @@ typedef struct {
     int32_t renormalize;
     const void *x;
     const float *logits;
+    const void *w_router;
     const void *const *w_gate;
     const void *const *w_up;
     const void *const *w_down;
@@ -363,7 +366,8 @@ enum {
     CRAFT_K_GATEUP = 3,    /* grouped gate/up GEMM + SwiGLU (gathers its rows) */
     CRAFT_K_DOWN = 4,      /* grouped down GEMM */
     CRAFT_K_COMBINE = 5,   /* weighted combine */
-    CRAFT_K_COUNT = 6
+    CRAFT_K_GATE = 6,      /* gating network, when the forward computes the scores itself */
+    CRAFT_K_COUNT = 7
 };
 craft_status craft_timing_enable(int32_t level, int32_t max_forwards);
 craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_K_COUNT]);

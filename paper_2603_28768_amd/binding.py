@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcraft.so")
 
 CRAFT_F32, CRAFT_BF16 = 0, 1
 CRAFT_W_BF16, CRAFT_W_E4M3 = 0, 1
-KERNEL_NAMES = ["route", "scan", "dispatch", "gateup", "down", "combine"]
+KERNEL_NAMES = ["route", "scan", "dispatch", "gateup", "down", "combine", "gate"]
 
 c_i32, c_i64, c_vp, c_sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
 P = ctypes.POINTER
@@ -31,7 +31,7 @@ class PlanParams(ctypes.Structure):
 
 class FwdArgs(ctypes.Structure):
     _fields_ = [("dtype", c_i32), ("T", c_i64), ("H", c_i32), ("I", c_i32), ("k", c_i32),
-                ("renormalize", c_i32), ("x", c_vp), ("logits", c_vp), ("w_gate", c_vp),
+                ("renormalize", c_i32), ("x", c_vp), ("logits", c_vp), ("w_router", c_vp), ("w_gate", c_vp),
                 ("w_up", c_vp), ("w_down", c_vp), ("w_gateup_packed", c_vp), ("w_down_packed", c_vp),
                 ("weight_format", c_i32),
                 ("out", c_vp), ("ids", c_vp), ("topk_w", c_vp),
@@ -347,7 +347,7 @@ class RankForward:
                  k: int, w_gate: Sequence, w_up: Sequence, w_down: Sequence,
                  renormalize: bool = True, max_rows: int = 0, device="cuda:0",
                  want_debug_outputs: bool = False, packed: Optional[Sequence] = None,
-                 weight_format: int = 0):
+                 weight_format: int = 0, w_router=None):
         import torch
         self.plan, self.layer, self.rank = plan, layer, rank
         self.dtype, self.T, self.H, self.I, self.k = dtype, T, H, I, k
@@ -389,6 +389,13 @@ class RankForward:
             a.w_gateup_packed, a.w_down_packed = self._packed[1].data_ptr(), self._packed[2].data_ptr()
             a.weight_format = weight_format
         a.out = self.out.data_ptr()
+        # scores come with every call, unless the forward runs the gating network itself
+        self.w_router = w_router
+        if w_router is not None:
+            assert w_router.dtype == td and tuple(w_router.shape) == (plan.E, H) and w_router.is_contiguous()
+            a.w_router = w_router.data_ptr()
+        else:
+            a.logits = self.out.data_ptr()       # stands in for "given" while the workspace is sized
         for name, t in self.debug.items():
             setattr(a, name, t.data_ptr())
         a.max_rows = max_rows
@@ -401,14 +408,20 @@ class RankForward:
         a.workspace_bytes = n.value
         self.args = a
 
-    def __call__(self, x, logits, stream=None):
-        """Enqueue one forward; returns the (reused) output tensor."""
+    def __call__(self, x, logits=None, stream=None):
+        """Enqueue one forward; returns the (reused) output tensor.  `logits` is left out by a
+        forward that was given the gate's weights."""
         import torch
         assert x.dtype == _torch_dtype(self.dtype) and tuple(x.shape) == (self.T, self.H)
-        assert logits.dtype == torch.float32 and tuple(logits.shape) == (self.T, self.plan.E)
-        assert x.is_contiguous() and logits.is_contiguous()
+        assert x.is_contiguous()
         self.args.x = x.data_ptr()
-        self.args.logits = logits.data_ptr()
+        if self.w_router is None:
+            assert logits.dtype == torch.float32 and tuple(logits.shape) == (self.T, self.plan.E)
+            assert logits.is_contiguous()
+            self.args.logits = logits.data_ptr()
+        else:
+            assert logits is None
+            self.args.logits = None
         _check(lib().craft_moe_rank_forward(self.plan._h, self.layer, self.rank,
                                             ctypes.byref(self.args), _stream_ptr(stream)),
                "craft_moe_rank_forward")

@@ -20,12 +20,20 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- workspace layout of one forward -------------------------------------------------
 struct Layout {
-    size_t ctrl, ids, w, lrank, dest, src, hist, chunk_tot, chunk_base, counts, slot_cnt, slot_off, mt_start, order, act, y, total;
+    size_t ctrl, ids, w, lrank, dest, src, hist, chunk_tot, chunk_base, gate_logits, gate_ws, gate_ws_bytes, counts, slot_cnt, slot_off, mt_start, order, act, y, total;
     int64_t max_rows, NB;
 };
 
+int cached_num_cu();
+
+size_t gate_workspace_bytes(int32_t dtype, int64_t T, int32_t H, int32_t E) {
+    int nxf = 1, nsplit = 1;
+    if (dtype == CRAFT_BF16 && T > 0) router_logits_shape(T, H, E, cached_num_cu(), true, &nxf, &nsplit);
+    return nsplit > 1 ? (size_t)nsplit * (size_t)T * (size_t)E * sizeof(float) : 0;
+}
+
 Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, int32_t H, int32_t I,
-                   int32_t dtype, int64_t max_rows_arg) {
+                   int32_t dtype, int64_t max_rows_arg, bool own_gate) {
     Layout L;
     const int64_t A = T * k;
     const size_t es = dtype == CRAFT_BF16 ? 2 : 4;
@@ -44,6 +52,10 @@ Layout make_layout(int64_t T, int32_t k, int32_t E, int32_t S, int32_t nslots, i
     const size_t chunks = (size_t)(L.NB + kScanChunk - 1) / kScanChunk;
     L.chunk_tot = take(chunks * E * 4);
     L.chunk_base = take(chunks * E * 4);
+    // scores and the split gate's partial scores, when the forward runs the gating network
+    L.gate_ws_bytes = own_gate ? gate_workspace_bytes(dtype, T, H, E) : 0;
+    L.gate_logits = take(own_gate ? (size_t)T * E * 4 : 0);
+    L.gate_ws = take(L.gate_ws_bytes);
     L.counts = take((size_t)E * 4);
     L.slot_cnt = take((size_t)S * 4);
     L.slot_off = take((size_t)(S + 1) * 4);
@@ -243,9 +255,7 @@ craft_status craft_router_logits_workspace(int32_t dtype, int64_t T, int32_t H, 
                                            size_t *bytes) {
     if (!bytes || (dtype != CRAFT_F32 && dtype != CRAFT_BF16)) return CRAFT_EINVAL;
     if (T < 0 || H <= 0 || E <= 0 || E > 1024 || (dtype == CRAFT_BF16 && H % 8)) return CRAFT_EINVAL;
-    int nxf = 1, nsplit = 1;
-    if (dtype == CRAFT_BF16 && T > 0) router_logits_shape(T, H, E, cached_num_cu(), true, &nxf, &nsplit);
-    *bytes = nsplit > 1 ? (size_t)nsplit * (size_t)T * (size_t)E * sizeof(float) : 0;
+    *bytes = gate_workspace_bytes(dtype, T, H, E);
     return CRAFT_OK;
 }
 
@@ -378,7 +388,7 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
     const craft_layer_plan &lp = plan->layers[layer];
     const int32_t nslots = lp.rank_slot_off[rank + 1] - lp.rank_slot_off[rank];
     Layout L = make_layout(a->T, a->k, plan->E, (int32_t)lp.slot_expert.size(), nslots, a->H, a->I,
-                           a->dtype, a->max_rows);
+                           a->dtype, a->max_rows, a->logits == nullptr);
     *bytes = L.total;
     return CRAFT_OK;
 }
@@ -400,11 +410,13 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     const int32_t E = plan->E, S = (int32_t)lp.slot_expert.size();
     const int32_t s_lo = lp.rank_slot_off[rank], s_hi = lp.rank_slot_off[rank + 1];
     const int32_t nslots = s_hi - s_lo;
-    Layout L = make_layout(a->T, a->k, E, S, nslots, a->H, a->I, a->dtype, a->max_rows);
+    const bool own_gate = a->logits == nullptr;
+    Layout L = make_layout(a->T, a->k, E, S, nslots, a->H, a->I, a->dtype, a->max_rows, own_gate);
     if (a->workspace_bytes < L.total) return CRAFT_EWORKSPACE;
     if (a->T > 0) {
-        if (!a->x || !a->logits || !a->out) return CRAFT_EINVAL;
-        if (!aligned(a->x, 16) || !aligned(a->out, 16) || !aligned(a->logits, 4)) return CRAFT_EINVAL;
+        if (!a->x || !a->out || (own_gate && !a->w_router)) return CRAFT_EINVAL;
+        if (!aligned(a->x, 16) || !aligned(a->out, 16)) return CRAFT_EINVAL;
+        if (own_gate ? !aligned(a->w_router, 16) : !aligned(a->logits, 4)) return CRAFT_EINVAL;
         const bool packed = a->w_gateup_packed && a->w_down_packed;
         if ((a->w_gateup_packed != nullptr) != (a->w_down_packed != nullptr)) return CRAFT_EINVAL;
         if (packed && a->dtype != CRAFT_BF16) return CRAFT_EINVAL;
@@ -437,13 +449,23 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     const tile_choice tiles = tiles_for(plan, layer, rank, a, packed);
     const int32_t *tables = static_cast<const int32_t *>(a->tables);
 
+    // 0 gating network, unless the scores are handed in
+    const float *logits = a->logits;
+    if (own_gate && a->T > 0) {
+        ScopedEvent ev(CRAFT_K_GATE, s);
+        float *own = reinterpret_cast<float *>(ws + L.gate_logits);
+        RouterArgs ga{a->dtype, a->x, a->w_router, a->T, a->H, E, own, cached_num_cu(),
+                      L.gate_ws_bytes ? reinterpret_cast<float *>(ws + L.gate_ws) : nullptr, 1};
+        if (launch_router_logits(ga, s) != hipSuccess) return CRAFT_EHIP;
+        logits = own;
+    }
     // 1 route (+ per-block ranks and counts); user copies of ids / weights are written by the
     // same kernel when asked for, so route straight into them and alias the workspace views
     int32_t *ids_out = a->ids ? a->ids : ids;
     float *w_out = a->topk_w ? a->topk_w : w;
     {
         ScopedEvent ev(CRAFT_K_ROUTE, s);
-        RouteArgs ra{a->logits, a->T, E, a->k, a->renormalize ? 1 : 0, ids_out, w_out, lrank, hist, ctrl};
+        RouteArgs ra{logits, a->T, E, a->k, a->renormalize ? 1 : 0, ids_out, w_out, lrank, hist, ctrl};
         if (launch_route(ra, s) != hipSuccess) return CRAFT_EHIP;
     }
     // 2 per-expert totals, slot offsets, tile table

@@ -61,7 +61,7 @@ class Case:
                                    self.rank_slot_off, rank, self.weights_of, True, tokens)
 
     def gpu_rank(self, rank: int, max_rows: int = 0, debug: bool = True, device="cuda:0",
-                 packed: bool = False):
+                 packed: bool = False, w_router=None):
         """(RankForward, x_dev, logits_dev) with this rank's weights resident; packed=True
         re-orders the weights with craft_pack_weights and runs the weight-streaming kernels."""
         import torch
@@ -81,7 +81,8 @@ class Case:
         fwd = binding.RankForward(self.plan, self.layer_index, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                                   wg, wu, wd, True, max_rows, device, want_debug_outputs=debug,
                                   packed=pk if packed else None,
-                                  weight_format=binding.CRAFT_W_E4M3 if (packed and self.w8) else 0)
+                                  weight_format=binding.CRAFT_W_E4M3 if (packed and self.w8) else 0,
+                                  w_router=w_router)
         x = binding.to_device(self.x, cfg.dtype, device)
         logits = torch.from_numpy(self.logits).to(device)
         return fwd, x, logits

@@ -163,6 +163,42 @@ def test_router_logits_full_size_feeds_the_router(torch_cuda, name):
     assert np.allclose(_np(w), ref_w, rtol=1e-5, atol=1e-30)
 
 
+@pytest.mark.parametrize("dtype,T,H,I,E,k,D,slots", [
+    ("bf16", 600, 512, 384, 32, 4, 4, 4),
+    ("bf16", 300, 2048, 64, 24, 2, 2, 2),        # the gate's contraction is split
+    ("f32", 200, 96, 64, 12, 3, 2, 2)])
+def test_forward_with_its_own_gating_network(torch_cuda, dtype, T, H, I, E, k, D, slots):
+    # scores not handed in: the forward runs the gate first.  Its scores are the ones the
+    # stand-alone call gives (same kernels, same workspace rule), and every decision after
+    # them is taken on those fp32 scores by library and checker alike.
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], dtype=dtype, T=T, H=H, I=I, E=E, k=k, D=D,
+                       replica_slots=slots, zipf_s=1.2, profile_batches=2)
+    case = Case(cfg)
+    Wr = synth.gate_weights(cfg)
+    Wrd = binding.to_device(Wr, dtype)
+    packed = dtype == "bf16"
+    for rank in range(D):
+        own, x, _ = case.gpu_rank(rank, packed=packed, w_router=Wrd)
+        out_own = own(x).clone()
+        ids_own = own.debug["ids"].clone()
+        logits = binding.router_logits(x, Wrd, binding.router_logits_workspace(x, Wrd))
+        given, _, _ = case.gpu_rank(rank, packed=packed)
+        out_given = given(x, logits)
+        torch.cuda.synchronize()
+        assert torch.equal(ids_own, given.debug["ids"]) and torch.equal(out_own, out_given)
+        scores = _np(logits)
+        want = oracle.router_logits(case.x, Wr)
+        assert np.abs(scores - want).max() <= GATE_TOL * np.abs(want).max()
+        ref = oracle.rank_forward(case.x, scores, cfg.k, case.slot_expert, case.rank_slot_off, rank,
+                                  case.weights_of, True, None)
+        assert np.array_equal(_np(ids_own), ref["ids"])
+        assert np.array_equal(_np(own.debug["dest"]).reshape(-1), ref["dest"])
+        assert own.result() == (ref["rows"], 0)
+        err = np.abs(_np(out_own).astype(np.float64) - ref["out"]).max()
+        assert err <= TOL[dtype] * np.abs(ref["out"]).max() + 1e-30
+
+
 # --------------------------------------------------------------------- forward
 
 def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False, knobs=None):
