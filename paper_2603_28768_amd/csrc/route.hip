@@ -77,25 +77,24 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
         const bool live = t < a.T;                 // uniform over the row
         const float *row = a.logits + (live ? t : 0) * a.E;
 
+        // Experts past E and experts already picked hold -inf: a finite score always beats
+        // them (k <= E, and scores are finite by contract).
+        constexpr float kGone = -__builtin_huge_valf();
         float v[NQ][4];
+        auto load_scores = [&]() {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            const int e0 = q * 64 + sub * 4;
-            if (vec_ok && e0 + 3 < a.E) {
-                const float4 f = *reinterpret_cast<const float4 *>(row + e0);
-                v[q][0] = f.x; v[q][1] = f.y; v[q][2] = f.z; v[q][3] = f.w;
-            } else {
+            for (int q = 0; q < NQ; ++q) {
+                const int e0 = q * 64 + sub * 4;
+                if (vec_ok && e0 + 3 < a.E) {
+                    const float4 f = *reinterpret_cast<const float4 *>(row + e0);
+                    v[q][0] = f.x; v[q][1] = f.y; v[q][2] = f.z; v[q][3] = f.w;
+                } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) v[q][c] = e0 + c < a.E ? row[e0 + c] : 0.0f;
+                    for (int c = 0; c < 4; ++c) v[q][c] = e0 + c < a.E ? row[e0 + c] : kGone;
+                }
             }
-        }
-        // bit (q*4+c) set = that expert is still available to this lane
-        uint64_t avail = 0;
-#pragma unroll
-        for (int q = 0; q < NQ; ++q)
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (q * 64 + sub * 4 + c < a.E) avail |= 1ull << (q * 4 + c);
+        };
+        load_scores();
 
         float pick_v[kMaxPickSlots];
         float first_v = 0.0f;
@@ -104,25 +103,31 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
             pick_v[s] = 0.0f;
             const int jn = min(16, a.k - s * 16);  // picks that land in slot s
             for (int j = 0; j < jn; ++j) {
-                float bv = 0.0f;
-                int bi = 0x7fffffff;               // no candidate: loses every comparison
-                bool have = false;
+                // the lane's best: a tournament in ascending expert order, the later entry
+                // winning only when strictly greater, so equal scores keep the lower id
+                float tv[NQ * 4];
+                int ti[NQ * 4];
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (((avail >> (q * 4 + c)) & 1ull) && (!have || v[q][c] > bv)) {
-                            bv = v[q][c];
-                            bi = q * 64 + sub * 4 + c;
-                            have = true;
-                        }
-                if (!have) bv = -__builtin_huge_valf();
+                    for (int c = 0; c < 4; ++c) { tv[q * 4 + c] = v[q][c]; ti[q * 4 + c] = q * 64 + sub * 4 + c; }
+#pragma unroll
+                for (int width = 1; width < NQ * 4; width *= 2)
+#pragma unroll
+                    for (int i = 0; i + width < NQ * 4; i += 2 * width)
+                        if (tv[i + width] > tv[i]) { tv[i] = tv[i + width]; ti[i] = ti[i + width]; }
+                float bv = tv[0];
+                int bi = ti[0];
                 argmax_step<kXor1>(bv, bi);
                 argmax_step<kXor2>(bv, bi);
                 argmax_step<kHalfMirror>(bv, bi);
                 argmax_step<kMirror>(bv, bi);
                 // the owner retires the pick; lane j of the row keeps it for the output
-                if (((bi >> 2) & 15) == sub) avail &= ~(1ull << ((bi >> 6) * 4 + (bi & 3)));
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (bi == q * 64 + sub * 4 + c) v[q][c] = kGone;
                 if (j == sub) { pick_v[s] = bv; my_id[s] = bi; }
                 if (s == 0 && j == 0) first_v = bv;       // the row maximum
             }
@@ -135,6 +140,7 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
             part += ex[s];
         }
         if (!a.renorm) {
+            load_scores();                         // the picks were blanked out: read the row again
             part = 0.0f;
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
