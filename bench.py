@@ -314,7 +314,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU's share (the heaviest simulated rank); "
-            "--gpus above 1 is not part of this build")
+            "--gpus above 1 is not supported: there are no collectives here")
         sys.exit(2)
 
     import torch                        # before the library: both must share one HIP runtime
