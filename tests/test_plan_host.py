@@ -259,3 +259,32 @@ def test_ffn_tile_heights_query():
     assert query() == 0
     assert (gu.value, dn.value, rgu.value, rdn.value) == (32, 32, 0, 0)
     assert query(9) == -1
+
+
+def test_gate_workspace_query_and_forward_workspace_with_own_gate():
+    # host-side sizes only; no device work
+    lib = binding.lib()
+    n = ctypes.c_size_t()
+    assert lib.craft_router_logits_workspace(binding.CRAFT_F32, 4096, 4096, 128, ctypes.byref(n)) == 0
+    assert n.value == 0                                        # the fp32 gate is never split
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 4096, 4096, 128, ctypes.byref(n)) == 0
+    assert n.value % (4096 * 128 * 4) == 0 and 1 < n.value // (4096 * 128 * 4) <= 8   # whole partial score matrices
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 1 << 20, 4096, 128, ctypes.byref(n)) == 0
+    assert n.value == 0                                        # enough tiles of tokens: nothing to split
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 0, 4096, 128, ctypes.byref(n)) == 0 and n.value == 0
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 16, 4100, 128, ctypes.byref(n)) == -1   # H % 8
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 16, 4096, 1025, ctypes.byref(n)) == -1  # E limit
+    assert lib.craft_router_logits_workspace(7, 16, 4096, 128, ctypes.byref(n)) == -1
+    # a forward that runs the gate itself needs room for the scores and the gate's workspace
+    g = np.random.default_rng(4)
+    W = g.multinomial(8 * 4096, synth.popularity(128, 1.0, 2, 0), size=(4, 1)).astype(np.int64)
+    plan = binding.Plan(W, 8, 8)
+    a = binding.FwdArgs()
+    a.dtype, a.T, a.H, a.I, a.k = 1, 4096, 4096, 1536, 8
+    a.logits = 0x1000                                          # scores handed in
+    given, own = ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.craft_moe_rank_forward_workspace(plan._h, 0, 0, ctypes.byref(a), ctypes.byref(given)) == 0
+    a.logits = None
+    assert lib.craft_moe_rank_forward_workspace(plan._h, 0, 0, ctypes.byref(a), ctypes.byref(own)) == 0
+    assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 4096, 4096, 128, ctypes.byref(n)) == 0
+    assert own.value - given.value >= 4096 * 128 * 4 + n.value
