@@ -89,6 +89,10 @@ def setup(cfg, dev="cuda:0", packed=True, e4m3=False):
                 host_logits=logits, host_w=host_w)
 
 
+def lay_slots(st):
+    return st["lay"]["slot_expert"]
+
+
 def cpu_baseline(cfg, st, budget_s=15.0):
     """The CPU checker on this host: routing, dispatch and combine on the whole batch, the
     FFN on a sample of the rank's rows sized to about `budget_s` seconds, scaled to all rows."""
@@ -393,6 +397,18 @@ def main():
                roofline=roof)
     if args.timing_level == 2:
         out["kernel_ms"] = {k: v["ms"] / max(v["launches"], 1) for k, v in times.items()}
+        # algorithmic bytes (and FLOPs of the two GEMMs) per launch of every kernel of the forward
+        A, S = cfg.T * cfg.k, len(lay_slots(st))
+        NB = (cfg.T + 31) // 32
+        alg = dict(route=(cfg.T * cfg.E * 4 + A * 9 + NB * cfg.E * 4, 0.0),
+                   scan=(2 * NB * cfg.E * 4 + S * 16, 0.0),
+                   dispatch=(A * 9 + A * 8, 0.0),
+                   gateup=(gu_bytes, gu_flops),
+                   down=(live * cfg.H * cfg.I * wes + M * cfg.I * es + M * cfg.H * es, 2.0 * cfg.H * cfg.I * M),
+                   combine=(M * cfg.H * es + cfg.T * cfg.H * es + A * 8, 0.0))
+        out["kernels"] = {k: dict(ms=out["kernel_ms"][k], algorithmic_bytes=b, gbs=b / (out["kernel_ms"][k] * 1e-3) / 1e9,
+                                  **({"tflops": f / (out["kernel_ms"][k] * 1e-3) / 1e12} if f else {}))
+                          for k, (b, f) in alg.items() if out["kernel_ms"].get(k, 0) > 0}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, st)
     print(json.dumps(out), flush=True)
