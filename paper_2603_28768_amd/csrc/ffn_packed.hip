@@ -180,7 +180,12 @@ template <bool GATEUP, int NGT, int NF, bool W8>
 __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t, const f32x16_t (&acc)[NGT][NF],
                                                 const float *wscale, int group0, int N, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
-    const int lane = threadIdx.x & 63;
+    // the lane's row and column offsets are derived here, after the contraction loop: shared
+    // with values from before it they would sit in scratch through the loop, and every reload
+    // would wait for the stores issued so far (loads and stores share one counter)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
 #pragma unroll
