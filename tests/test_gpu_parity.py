@@ -419,6 +419,25 @@ def test_rank_with_more_slots_than_the_tile_tables_in_lds(torch_cuda):
     _check_rank(torch_cuda, case, 0, packed=False)
 
 
+@pytest.mark.parametrize("T,E,k,D,slots", [
+    (3000, 160, 4, 4, 6),        # three expert groups share the waves five each; 19 blocks per wave
+    (4100, 128, 8, 8, 16),       # two groups, 17 blocks per wave: one more than the registers keep
+    (8192, 384, 8, 8, 24),       # six groups, 128 blocks per wave, four waves idle
+    (2000, 1024, 2, 16, 32),     # a wave per group, every block of the batch
+    (8200, 72, 4, 2, 5),         # one block more than a chunk: two workgroups per group, ragged group
+    (20000, 200, 3, 4, 9)])      # three chunks of four groups
+def test_dispatch_over_block_and_expert_shapes(torch_cuda, T, E, k, D, slots):
+    # how the per-block counts are dealt to the waves depends on the number of 32-token blocks
+    # and of 64-expert groups: integer results against the checker on every rank, narrow FFN
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=T, H=64, I=32, E=E, k=k, D=D, replica_slots=slots,
+                       zipf_s=1.0, profile_batches=2)
+    print("dispatch shapes", cfg, flush=True)
+    case = Case(cfg)
+    toks = list(range(0, T, max(1, T // 16)))
+    for g in (0, D - 1):
+        _check_rank(torch_cuda, case, g, tokens=toks, packed=True)
+
+
 @pytest.mark.parametrize("w8", [False, True])
 @pytest.mark.parametrize("T,H,I,E,k,D,slots,zipf", [
     (240, 128, 192, 32, 4, 1, 0, 1.0),     # fewer busy tiles than units of the two-fragment slots
