@@ -152,3 +152,67 @@ def test_window_accumulated_on_device_and_replan(torch_cuda):
     assert rows == r["rows"] and ovf == 0
     assert np.array_equal(f2.debug["dest"].cpu().numpy().reshape(-1), r["dest"])
     assert np.abs(out - r["out"]).max() <= 1e-2 * np.abs(r["out"]).max()
+
+
+@pytest.mark.gpu
+def test_weights_relocated_on_a_side_stream_while_the_old_plan_serves(torch_cuda):
+    # Sec. 4.3 step 3 asks for the relocation not to stall serving: the experts the new plan
+    # brings to this rank are copied from pinned host memory and packed on a second stream
+    # while forwards under the old plan keep running on the first; the serving stream waits
+    # for one event, then runs under the new plan with the second set of buffers.
+    torch = torch_cuda
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=768, H=512, I=256, E=48, D=4, replica_slots=6,
+                       profile_batches=2)
+    case = Case(cfg)
+    rank = case.heaviest
+    fwd, x, logits = case.gpu_rank(rank, packed=True)
+    ref_old = case.oracle_rank(rank)
+    pop1 = np.roll(case.pop, 17)                                     # the workload shifts
+    ids, _ = oracle.route(synth.router_logits(cfg, pop1, "window", 0), cfg.k)
+    want = np.bincount(ids.reshape(-1), minlength=cfg.E).astype(np.int64)
+    fresh = binding.Plan(want[None, None, :], cfg.D, cfg.replica_slots)
+    d = case.plan.diff(fresh, 0, rank)
+    after = Case(cfg, plan=fresh, pop=pop1)
+    old_slots, new_slots = case.rank_slots(rank), after.rank_slots(rank)
+    assert d["n_fetch"] > 0 and (d["reuse"] >= 0).any()
+    # the experts to fetch wait in pinned host memory, as the paper's CPU-resident weights do
+    host = {}
+    for j, e in enumerate(new_slots):
+        if d["reuse"][j] < 0 and e not in host:
+            host[e] = [torch.from_numpy(np.ascontiguousarray(m, dtype=np.float32)).to(torch.bfloat16).pin_memory()
+                       for m in synth.expert_weights(cfg, e)]
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    (og, ou, od), opacked = fwd._weights, fwd._packed[0]
+    wg, wu, wd, pk = [None] * len(new_slots), [None] * len(new_slots), [None] * len(new_slots), [None] * len(new_slots)
+    outs = [fwd(x, logits).clone()]
+    side.wait_stream(main)
+    for j, e in enumerate(new_slots):
+        if d["reuse"][j] >= 0:
+            continue
+        with torch.cuda.stream(side):
+            dev = [m.to("cuda:0", non_blocking=True) for m in host[e]]
+        wg[j], wu[j], wd[j] = dev
+        pk[j] = binding.pack_weights(*dev, stream=side)
+        outs.append(fwd(x, logits, stream=main).clone())              # serving goes on meanwhile
+    arrived = side.record_event()
+    for j, e in enumerate(new_slots):
+        r = int(d["reuse"][j])
+        if r >= 0:
+            assert old_slots[r] == e
+            wg[j], wu[j], wd[j], pk[j] = og[r], ou[r], od[r], opacked[r]
+    main.wait_event(arrived)
+    swapped = binding.RankForward(fresh, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k, wg, wu, wd,
+                                  want_debug_outputs=True, packed=pk)
+    xs = binding.to_device(after.x, cfg.dtype)
+    out_new = swapped(xs, torch.from_numpy(after.logits).to("cuda:0")).float().cpu().numpy().astype(np.float64)
+    torch.cuda.synchronize()
+    # every forward under the old plan gave the same bits, and they are the checker's answer
+    first = outs[0].float().cpu().numpy().astype(np.float64)
+    assert len(outs) == 1 + d["n_fetch"]
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    assert np.abs(first - ref_old["out"]).max() <= 1e-2 * np.abs(ref_old["out"]).max()
+    r = after.oracle_rank(rank)
+    assert swapped.result() == (r["rows"], 0)
+    assert np.array_equal(swapped.debug["dest"].cpu().numpy().reshape(-1), r["dest"])
+    assert np.abs(out_new - r["out"]).max() <= 1e-2 * np.abs(r["out"]).max()
