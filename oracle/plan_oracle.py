@@ -27,7 +27,8 @@ Steps and where they come from:
                         placement for each candidate replica count; per-layer mean
                         balancedness gain over placement-only.
   choose_replication_factor  Sec. 4.2.1 step 2: the R with the highest balancedness
-                        gain per replica.
+                        gain per replica (parity unpinned: the paper gives no rule,
+                        the tests pin this reading only).
   make_plan_paper       the paper's own pipeline: Alg. 1 -> (R) -> Alg. 2 -> Alg. 3 ->
                         placement.
   plan_diff             Sec. 4.3 step 3: the weights a rank must fetch or may drop when
@@ -344,7 +345,9 @@ def choose_replication_factor(Tmap: Dict[int, Sequence[float]], D: int, R_max: i
     """Sec. 4.2.1 step 2, automatic mode: the replication factor R in 1..R_max whose best
     allocation of R * D replicas has the highest total gain per replica (exact-sum
     allocations as in Alg. 2; an R no selection sums to is skipped; ties keep the
-    smaller R).  Returns 0 when no R in range is reachable."""
+    smaller R).  Returns 0 when no R in range is reachable.
+    Parity unpinned against the paper, which does not give the rule: the tests pin this
+    reading of the sentence by brute force over all allocations, not the paper's choice."""
     best_tab = mckp_table(Tmap, R_max * D)
     best_R, best_v = 0, 0.0
     for R in range(1, R_max + 1):
