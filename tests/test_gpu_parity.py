@@ -319,6 +319,24 @@ def test_forward_replays_from_a_hip_graph(torch_cuda):
     assert np.abs(out - ref["out"]).max() <= TOL[cfg.dtype] * np.abs(ref["out"]).max()
 
 
+def test_one_expert_layer_is_the_dense_ffn(torch_cuda):
+    # E = 1, k = 1: every token goes to the one expert with weight 1, which is how a dense
+    # (shared) expert runs through the same entry point.  Alone on one rank the layer is the
+    # plain SwiGLU FFN of every token; replicated on two ranks each takes every other token
+    # (the i-th assignment goes to copy i mod 2) and the two outputs add up to it.
+    for D, slots in ((1, 0), (2, 1)):
+        cfg = synth.scaled(synth.CONFIGS["qwen3"], T=600, H=512, I=384, E=1, k=1, D=D,
+                           replica_slots=slots, profile_batches=2)
+        case = Case(cfg)
+        dense = oracle.ffn_rows(case.x.astype(np.float32), *synth.expert_weights(cfg, 0))
+        total = np.zeros_like(dense)
+        for g in range(D):
+            out, ref = _check_rank(torch_cuda, case, g, packed=True)
+            assert ref["rows"] == cfg.T // D
+            total += out
+        assert np.abs(total - dense).max() <= TOL["bf16"] * np.abs(dense).max()
+
+
 def test_rank_without_rows_and_unused_experts(torch_cuda):
     # strong skew on few tokens: some experts (and with D = E some ranks) get nothing
     cfg = synth.scaled(synth.CONFIGS["qwen3"], T=24, H=128, I=64, E=16, k=2, D=16,
