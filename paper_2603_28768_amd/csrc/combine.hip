@@ -122,7 +122,13 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (inside[u]) *reinterpret_cast<uint4 *>(out + c0[u]) = Chunk<T>::pack(acc[u]);
+            if (inside[u]) {
+                // written once and not read again by this launch: a streaming store
+                typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+                const uint4 q = Chunk<T>::pack(acc[u]);
+                const u32x4 v = {q.x, q.y, q.z, q.w};
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + c0[u]));
+            }
     }
 }
 

@@ -17,6 +17,7 @@ struct Tile {
     int32_t n0;        // first output column
     int32_t pos0;      // global dispatch position of the slot's first row
     int32_t mtile;     // index of the row-tile in the list of all row-tiles of the busy slots
+    int32_t single;    // 1 when this is the slot's only row-tile (nobody else reads its weights)
 };
 
 // Flattened work item w -> tile.  nt = column tiles per slot, bn = columns per tile.
@@ -67,6 +68,7 @@ static __device__ __forceinline__ Tile decode_tile_in(int32_t nslots, const MT &
     t.rows = min(f1 * 32, slot_rows) - t.m0;
     t.n0 = (rem / mts) * bn;
     t.mtile = mt_first + i;
+    t.single = mts == 1 ? 1 : 0;
     return t;
 }
 static __device__ __forceinline__ Tile decode_tile(const FfnArgs &a, const int32_t *mt_start, int64_t w,

@@ -84,6 +84,13 @@ template <> __device__ __forceinline__ u32x2_t zero_fragment<true>() {
     return z;
 }
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
+// A weight fragment that no other tile of the launch reads (a cold slot's: it has one
+// row-tile): a streaming load, which leaves the L2 to the weights and rows that are shared.
+template <bool ONCE, typename P>
+static __device__ __forceinline__ auto wload(P p) -> decltype(*p + *p) {
+    if (ONCE) return __builtin_nontemporal_load(p);
+    return *p;
+}
 
 // One 16-wide contraction step of NGT x NXF MFMAs (NGT column groups per wave).  A wave is alone on its SIMD, so whatever
 // it issues between two MFMAs delays the second one unless it fits into the 32 cycles the
@@ -100,7 +107,7 @@ typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
 //                         column group of that slot's weights (a ring of its own): one more
 //                         MFMA at the end of the last group's, its LDS read behind that
 //                         group's first MFMA, its refill behind itself
-template <int NXF, int NGT, int R, int RR, int PW, int PHASE, bool W8, bool RIDER>
+template <int NXF, int NGT, int R, int RR, int PW, int PHASE, bool W8, bool RIDER, bool ONCE>
 __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, typename WStream<W8>::type wp,
                                             typename WStream<W8>::type wpr, int64_t wstride,
                                             typename WFrag<W8>::type (&wq)[NGT][PW],
@@ -132,9 +139,9 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
                     if ((g & 1) == 1 || g == NXA - 1) XR[i] = xin[(size_t)xp[i] + koff];
                 }
             }
-            if (g == NXF - 1) wq[n][R] = wp[nxt + n * 64];
+            if (g == NXF - 1) wq[n][R] = wload<ONCE>(wp + nxt + n * 64);
             if (RIDER && last && g == NXA - 1)
-                wr[RR % rider_ring(NXF, W8)] = wpr[min(step + rider_ring(NXF, W8), ksteps - 1) * wstride];
+                wr[RR % rider_ring(NXF, W8)] = wload<true>(wpr + min(step + rider_ring(NXF, W8), ksteps - 1) * wstride);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -146,7 +153,7 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
 // ahead is requested from global memory into the same registers; the last step already
 // fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
 // enough: a stage is rewritten a full slab after its last reader has passed a barrier.
-template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER>
+template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER, bool ONCE>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
                                             typename WStream<W8>::type wp, typename WStream<W8>::type wpr,
@@ -161,11 +168,11 @@ __device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, i
     const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8) >> 3;
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER>(xs + 32, ks * 4 + 0, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER>(xs + 64, ks * 4 + 1, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER, ONCE>(xs + 32, ks * 4 + 0, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER, ONCE>(xs + 64, ks * 4 + 1, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
     __syncthreads();
-    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER>(xs + 96, ks * 4 + 2, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER, ONCE>(xs + 96, ks * 4 + 2, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER, ONCE>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
 }
 
 // Epilogue of NF accumulator fragments x NGT column groups, which are the rows of tile t from
@@ -247,7 +254,7 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
 // One tile with NXF live 32-row activation fragments of its own slot and, with RIDER, one more
 // fragment of a cold slot (tile r: up to 32 rows, half a column tile starting at r.n0) that
 // meets one column group of that slot's weights per wave.
-template <bool GATEUP, int NXF, int NGT, bool W8, bool RIDER>
+template <bool GATEUP, int NXF, int NGT, bool W8, bool RIDER, bool ONCE>
 __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, const Tile &r, unsigned char *smem,
                                             int K, int N, int ngroups, int nk4, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
@@ -306,10 +313,10 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
 #pragma unroll
         for (int j = 0; j < PW / 2; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE>(wp + j * wstride + n * 64);
         if (RIDER)
 #pragma unroll
-            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wpr[j * wstride];
+            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wload<true>(wpr + j * wstride);
         if (!RIDER) wr[0] = zero_fragment<W8>();    // a placeholder that no MFMA reads
         const int k0 = min(kc * 8, K - 8) >> 3, k1 = min(64 + kc * 8, K - 8) >> 3;
 #pragma unroll
@@ -320,10 +327,10 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
 #pragma unroll
         for (int j = PW / 2; j < PW; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wp[j * wstride + n * 64];
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE>(wp + j * wstride + n * 64);
         if (RIDER)
 #pragma unroll
-            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wpr[j * wstride];
+            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wload<true>(wpr + j * wstride);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NXA; ++i)
@@ -341,10 +348,10 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
         unsigned char *s0 = smem + st * XSTAGEB;
         unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
         unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
-        packed_slab<NXF, NGT, 0, PW, W8, RIDER>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 1, PW, W8, RIDER>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 2, PW, W8, RIDER>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 3, PW, W8, RIDER>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 0, PW, W8, RIDER, ONCE>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 1, PW, W8, RIDER, ONCE>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 2, PW, W8, RIDER, ONCE>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 3, PW, W8, RIDER, ONCE>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
         st = (st + 1) % 3;
     }
 
@@ -357,6 +364,14 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
             a, r, accr, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase_r) + scale_off),
             group_r, N, lo_pos);
 }
+
+// a busy slot's tile of F fragments, with or without a rider; the weights of a slot with a single
+// row-tile are read by this tile alone and streamed
+#define HOT(F, RIDE)                                                                                   \
+    do {                                                                                               \
+        if (t.single) packed_tile<GATEUP, F, NG, W8, RIDE, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos);   \
+        else packed_tile<GATEUP, F, NG, W8, RIDE, false>(a, t, r, smem, K, N, ngroups, nk4, lo_pos);           \
+    } while (0)
 
 template <bool GATEUP, bool W8>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
@@ -398,6 +413,7 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
         t.m0 = 0;
         t.n0 = 0;
         t.mtile = 0;
+        t.single = 1;
         return t;
     };
 
@@ -418,24 +434,24 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
             }
             if (ride) {
                 switch (frags) {
-                    case 1: packed_tile<GATEUP, 1, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 2: packed_tile<GATEUP, 2, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 3: packed_tile<GATEUP, 3, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 4: packed_tile<GATEUP, 4, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 5: packed_tile<GATEUP, 5, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 6: packed_tile<GATEUP, 6, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
-                    default: packed_tile<GATEUP, 7, NG, W8, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 1: HOT(1, true); break;
+                    case 2: HOT(2, true); break;
+                    case 3: HOT(3, true); break;
+                    case 4: HOT(4, true); break;
+                    case 5: HOT(5, true); break;
+                    case 6: HOT(6, true); break;
+                    default: HOT(7, true); break;
                 }
             } else {
                 switch (frags) {
-                    case 1: packed_tile<GATEUP, 1, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 2: packed_tile<GATEUP, 2, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 3: packed_tile<GATEUP, 3, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 4: packed_tile<GATEUP, 4, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 5: packed_tile<GATEUP, 5, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 6: packed_tile<GATEUP, 6, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    case 7: packed_tile<GATEUP, 7, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
-                    default: packed_tile<GATEUP, 8, NG, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos); break;
+                    case 1: HOT(1, false); break;
+                    case 2: HOT(2, false); break;
+                    case 3: HOT(3, false); break;
+                    case 4: HOT(4, false); break;
+                    case 5: HOT(5, false); break;
+                    case 6: HOT(6, false); break;
+                    case 7: HOT(7, false); break;
+                    default: HOT(8, false); break;
                 }
             }
         } else {
@@ -448,8 +464,8 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
             Tile t = slot_tile(hot + c);
             t.n0 = (int32_t)(v % (2 * nt)) * (BN / 2);
             if (t.n0 < N) {                        // the last half may lie past the matrix
-                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
-                else packed_tile<GATEUP, 2, 1, W8, false>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
+                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
+                else packed_tile<GATEUP, 2, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
             }
         }
         if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
