@@ -31,6 +31,9 @@
 //     8 KB of weights plus 1 KB per row fragment into it: at 256 x 256 the tile needs those
 //     bytes about as fast as the MFMAs consume them, below that it is bound by them.  Only
 //     fewer bytes per flop make it faster (8-bit weights); deeper rings do not.
+//   * Weight fragments that a single tile reads (a cold slot's, a rider's, a busy slot's with
+//     one row-tile) are requested with streaming loads, so that the L2 keeps the activation
+//     rows and the weights that several tiles share.
 //   * Row fragments beyond a tile's valid rows are skipped entirely (loads, LDS traffic,
 //     MFMAs): a slot with 20 rows costs one eighth of the matrix work of a full tile while
 //     streaming the same weights.
