@@ -56,17 +56,20 @@ __global__ __launch_bounds__(kThreads) void expert_load_kernel(LoadArgs a, int32
     while (head < c1 && ((first + head) & 3)) ++head;
     for (int64_t i = c0 + threadIdx.x; i < head; i += kThreads) bump(ids[i]);
     const int64_t nvec = (c1 - head) / 4;
-    const int4 *v = reinterpret_cast<const int4 *>(ids + head);
+    // the trace is read once: streaming loads
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    const i32x4 *v = reinterpret_cast<const i32x4 *>(ids + head);
     int64_t i = threadIdx.x;
     for (; i + 3 * kThreads < nvec; i += 4 * kThreads) {
-        const int4 q0 = v[i], q1 = v[i + kThreads], q2 = v[i + 2 * kThreads], q3 = v[i + 3 * kThreads];
+        const i32x4 q0 = __builtin_nontemporal_load(v + i), q1 = __builtin_nontemporal_load(v + i + kThreads),
+                    q2 = __builtin_nontemporal_load(v + i + 2 * kThreads), q3 = __builtin_nontemporal_load(v + i + 3 * kThreads);
         bump(q0.x); bump(q0.y); bump(q0.z); bump(q0.w);
         bump(q1.x); bump(q1.y); bump(q1.z); bump(q1.w);
         bump(q2.x); bump(q2.y); bump(q2.z); bump(q2.w);
         bump(q3.x); bump(q3.y); bump(q3.z); bump(q3.w);
     }
     for (; i < nvec; i += kThreads) {
-        const int4 q = v[i];
+        const i32x4 q = __builtin_nontemporal_load(v + i);
         bump(q.x); bump(q.y); bump(q.z); bump(q.w);
     }
     for (int64_t j = head + nvec * 4 + threadIdx.x; j < c1; j += kThreads) bump(ids[j]);
