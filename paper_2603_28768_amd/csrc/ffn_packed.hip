@@ -87,6 +87,15 @@ template <> __device__ __forceinline__ u32x2_t zero_fragment<true>() {
     return z;
 }
 typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
+// The lane's index inside its wave, counted afresh from the execution mask: with the wave's
+// index kept in a scalar register no vector register has to carry the thread index through
+// the contraction loops (it was spilled there, and its reload at the start of the epilogue
+// waited for every request still in flight).
+static __device__ __forceinline__ int lane_index() {
+    int lane;                                      // volatile: counted where it is used, never kept
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane));
+    return lane;
+}
 // A weight fragment that no other tile of the launch reads (a cold slot's: it has one
 // row-tile): a streaming load, which leaves the L2 to the weights and rows that are shared.
 template <bool ONCE, typename P>
@@ -193,9 +202,7 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
     // the lane's row and column offsets are derived here, after the contraction loop: shared
     // with values from before it they would sit in scratch through the loop, and every reload
     // would wait for the stores issued so far (loads and stores share one counter)
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
-    const int lane = tid & 63;
+    const int lane = lane_index();
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
 #pragma unroll
@@ -258,17 +265,17 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
 // fragment of a cold slot (tile r: up to 32 rows, half a column tile starting at r.n0) that
 // meets one column group of that slot's weights per wave.
 template <bool GATEUP, int NXF, int NGT, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, const Tile &r, unsigned char *smem,
-                                            int K, int N, int ngroups, int nk4, int32_t lo_pos) {
+__device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, const Tile &r, unsigned char *smem,
+                                               int K, int N, int ngroups, int nk4, int32_t lo_pos, int32_t *counter,
+                                               int wave_id) {
     constexpr int GC = GATEUP ? 16 : 32;
     constexpr int NXA = NXF + (RIDER ? 1 : 0);
     constexpr int PW = ring_depth(NXA);
     // The lane's constants (LDS offsets and the like) are derived afresh in every tile: hoisted
     // out of the tile loop they would stay live through the tallest tile, which has no
     // register to spare, and come back from scratch inside every contraction loop.
-    int tid = threadIdx.x;
-    asm volatile("" : "+v"(tid));
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = lane_index(), wave = wave_id;
+    const int tid = wave * 64 + lane;
     const int lr = tid >> 3, kc = tid & 7;
     const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
     const int ksteps = nk4 * 16;
@@ -358,6 +365,12 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
         st = (st + 1) % 3;
     }
 
+    // The next work item is claimed before the epilogue and looked at after it: the counter's
+    // round trip runs while the results are converted and stored.
+    // (an increment rather than an add: the compiler rewrites an add of a uniform value into a
+    // wave-wide reduction whose result it waits for on the spot)
+    int32_t claimed = 0;
+    if (tid == 0) claimed = (int32_t)atomicInc(reinterpret_cast<unsigned int *>(counter), 0xffffffffu);
     const size_t scale_off = (size_t)groups_padded * ksteps * 512;   // E4M3: row scales behind the codes
     store_fragments<GATEUP, NGT, NXF, W8>(
         a, t, acc, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase) + scale_off),
@@ -366,14 +379,15 @@ __device__ __forceinline__ void packed_tile(const FfnArgs &a, const Tile &t, con
         store_fragments<GATEUP, 1, 1, W8>(
             a, r, accr, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase_r) + scale_off),
             group_r, N, lo_pos);
+    return claimed;
 }
 
 // a busy slot's tile of F fragments, with or without a rider; the weights of a slot with a single
 // row-tile are read by this tile alone and streamed
 #define HOT(F, RIDE)                                                                                   \
     do {                                                                                               \
-        if (t.single) packed_tile<GATEUP, F, NG, W8, RIDE, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos);   \
-        else packed_tile<GATEUP, F, NG, W8, RIDE, false>(a, t, r, smem, K, N, ngroups, nk4, lo_pos);           \
+        if (t.single) claimed = packed_tile<GATEUP, F, NG, W8, RIDE, true>(a, t, r, smem, K, N, ngroups, nk4, lo_pos, counter, wave_id);   \
+        else claimed = packed_tile<GATEUP, F, NG, W8, RIDE, false>(a, t, r, smem, K, N, ngroups, nk4, lo_pos, counter, wave_id);           \
     } while (0)
 
 template <bool GATEUP, bool W8>
@@ -381,6 +395,7 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
     __shared__ int64_t next_item;
     __shared__ TileTables tt;
+    const int wave_id = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int32_t *mt_start = a.mt_start + (GATEUP ? 0 : a.nslots + 1);
     const bool small = a.nslots <= TileTables::kMaxSlots;
     if (small) load_tile_tables(a, mt_start, tt);
@@ -422,6 +437,7 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
 
     int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
+        int32_t claimed = 0;                       // thread 0: the counter's answer, fetched inside the tile
         if (w < hot_tiles) {
             const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax) : decode_tile(a, mt_start, w, nt, BN, fmax);
             const int frags = (t.rows + 31) >> 5;  // live 32-row fragments of this tile
@@ -467,11 +483,13 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
             Tile t = slot_tile(hot + c);
             t.n0 = (int32_t)(v % (2 * nt)) * (BN / 2);
             if (t.n0 < N) {                        // the last half may lie past the matrix
-                if (t.rows <= 32) packed_tile<GATEUP, 1, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
-                else packed_tile<GATEUP, 2, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos);
+                if (t.rows <= 32) claimed = packed_tile<GATEUP, 1, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos, counter, wave_id);
+                else claimed = packed_tile<GATEUP, 2, 1, W8, false, true>(a, t, t, smem, K, N, ngroups, nk4, lo_pos, counter, wave_id);
+            } else if (wave_id == 0 && lane_index() == 0) {
+                claimed = (int32_t)atomicInc(reinterpret_cast<unsigned int *>(counter), 0xffffffffu);
             }
         }
-        if (threadIdx.x == 0) next_item = (int64_t)gridDim.x + atomicAdd(counter, 1);
+        if (wave_id == 0 && lane_index() == 0) next_item = (int64_t)gridDim.x + claimed;
         __syncthreads();
         w = next_item;
         __syncthreads();
