@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
 """Throughput of one expert-parallel rank's MoE layer under a CRAFT replication plan.
 
-A step is one craft_moe_rank_forward call (route, load counts, replica-aware dispatch,
-grouped SwiGLU FFN, combine) on the heaviest simulated rank of the workload, inputs and
-weights resident in HBM.  The plan is made once before the timed region, through the
-library (GPU routing of the profiling batches -> craft_expert_load -> craft_plan), as the
-paper does at initialisation (Sec. 5.4: planning has no inference-time cost).
+A step is one pass of the hot path over one batch: craft_moe_rank_forward (route, load
+counts, replica-aware dispatch, grouped SwiGLU FFN, combine) on the heaviest simulated rank
+of every executed layer of the workload, inputs and weights resident in HBM.  The default
+workload is the largest one: the multi-layer stack (routing traces of 58 layers x 256 experts
+-> GPU histogram -> plan at 256 replicas -> four DeepSeek-V3-shaped layers at T = 32768, each
+under its own layer's plan); the single-layer workloads are behind --config.  The plan is
+made once before the timed region, through the library (craft_expert_load -> craft_plan), as
+the paper does at initialisation (Sec. 5.4: planning has no inference-time cost).
 
-Prints one JSON line: tokens/s of the layer, plus
+Prints one JSON line: tokens/s through an MoE layer, plus
   roofline      for the dominant kernel (grouped gate/up GEMM): algorithmic bytes and flops
-                per launch over its HIP-event duration measured inside the timed region
-  cpu_baseline  the CPU checker timed on this host on a bounded sample of the same rank
+                per launch over its HIP-event duration measured inside the timed region; the
+                per-slot bounds of the expert FFN; the other kernels' fractions; this
+                machine's own copy and MFMA-loop rates
+  cpu_baseline  the CPU checker timed on this host on a bounded sample of the same work
 """
 from __future__ import annotations
 
@@ -37,39 +42,45 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def setup(cfg, dev="cuda:0", packed=True, e4m3=False):
-    """Profiling -> plan -> evaluation batch -> heaviest rank, all through the library."""
+def setup(cfg, dev="cuda:0", packed=True, e4m3=False, plan=None, layer=0, pop=None, plan_ms=0.0,
+          keep_host_weights=True):
+    """Profiling -> plan -> evaluation batch -> heaviest rank, all through the library.
+    With `plan` (a multi-layer plan made elsewhere): the evaluation batch of its layer `layer`,
+    whose experts have popularity `pop`."""
     import torch
     from paper_2603_28768_amd import binding, synth
 
-    pop = synth.layer_popularity(cfg)
-    prof = np.concatenate([synth.router_logits(cfg, pop, "profile", b)
-                           for b in range(cfg.profile_batches)])
-    ids, _ = binding.route_topk(torch.from_numpy(prof).to(dev), cfg.k)
-    W = binding.expert_load(ids.reshape(1, -1, cfg.k), cfg.E, cfg.T)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    plan = binding.Plan(W.cpu().numpy(), cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
-    plan_ms = (time.perf_counter() - t0) * 1e3
+    if plan is None:
+        pop = synth.layer_popularity(cfg)
+        prof = np.concatenate([synth.router_logits(cfg, pop, "profile", b)
+                               for b in range(cfg.profile_batches)])
+        ids, _ = binding.route_topk(torch.from_numpy(prof).to(dev), cfg.k)
+        W = binding.expert_load(ids.reshape(1, -1, cfg.k), cfg.E, cfg.T)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        plan = binding.Plan(W.cpu().numpy(), cfg.D, cfg.replica_slots, gpus_per_node=cfg.gpus_per_node)
+        plan_ms = (time.perf_counter() - t0) * 1e3
 
-    logits = synth.router_logits(cfg, pop, "eval")
-    x = synth.activations(cfg)
+    logits = synth.router_logits(cfg, pop, "eval", layer=layer)
+    x = synth.activations(cfg, layer=layer)
     d_logits = torch.from_numpy(logits).to(dev)
     eids, _ = binding.route_topk(d_logits, cfg.k)
     counts = binding.expert_load(eids.reshape(1, -1, cfg.k), cfg.E, cfg.T)[0, 0].cpu().numpy()
-    rows, rank = plan.rank_rows(0, counts)
-    lay = plan.layer(0)
+    rows, rank = plan.rank_rows(layer, counts)
+    lay = plan.layer(layer)
     slots = [int(e) for e in lay["slot_expert"][lay["rank_slot_off"][rank]:lay["rank_slot_off"][rank + 1]]]
     host_w, dev_w = {}, {}
     for e in slots:
-        if e not in host_w:
-            host_w[e] = synth.expert_weights(cfg, e)
-            dev_w[e] = tuple(binding.to_device(m, cfg.dtype, dev) for m in host_w[e])
+        if e not in dev_w:
+            hw = synth.expert_weights(cfg, e, layer)
+            dev_w[e] = tuple(binding.to_device(m, cfg.dtype, dev) for m in hw)
+            if keep_host_weights:
+                host_w[e] = hw
     # model loading: weights are re-ordered once for the weight-streaming kernels
     packed = packed and cfg.dtype == "bf16"
     pack = binding.pack_weights_e4m3 if e4m3 else binding.pack_weights
     pk = {e: pack(*dev_w[e]) for e in dev_w} if packed else None
-    fwd = binding.RankForward(plan, 0, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
+    fwd = binding.RankForward(plan, layer, rank, cfg.dtype, cfg.T, cfg.H, cfg.I, cfg.k,
                               [dev_w[e][0] for e in slots], [dev_w[e][1] for e in slots],
                               [dev_w[e][2] for e in slots],
                               packed=[pk[e] for e in slots] if packed else None,
@@ -84,9 +95,40 @@ def setup(cfg, dev="cuda:0", packed=True, e4m3=False):
         n, c = int(counts[e]), int(lay["copies"][e])
         if lay["rank_slot_off"][rank] <= p < lay["rank_slot_off"][rank + 1]:
             slot_rows.append((n - q + c - 1) // c if n > q else 0)
-    return dict(plan=plan, plan_ms=plan_ms, lay=lay, rank=rank, rows=rows, slots=slots,
+    return dict(cfg=cfg, layer=layer, plan=plan, plan_ms=plan_ms, lay=lay, rank=rank, rows=rows, slots=slots,
                 slot_rows=slot_rows, fwd=fwd, x=d_x, logits=d_logits, host_x=x,
                 host_logits=logits, host_w=host_w)
+
+
+def setup_stack(dev="cuda:0", packed=True, e4m3=False):
+    """The multi-layer stack: routing traces of 58 layers x 256 experts (32768 tokens per layer,
+    profiling batches of 4096) -> craft_expert_load on the GPU -> craft_plan at 256 replicas over
+    32 ranks; then the four executed layers (largest, smallest and the two tercile Zipf
+    exponents), DeepSeek-V3-shaped at T = 32768, each under its own layer's plan.  Host weights
+    are kept for the first layer only (the CPU baseline's sample)."""
+    import torch
+    from paper_2603_28768_amd import binding, synth
+    L, E, K, D, idx = 58, 256, 8, 32, 5
+    s = synth.trace_layer_exponents(L, idx)
+    ids = np.stack([synth.routing_trace_layer(E, K, 32768, s[l], idx, l) for l in range(L)])
+    W = binding.expert_load(torch.from_numpy(ids).to(dev), E, 4096)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    plan = binding.Plan(W.cpu().numpy(), D, 256)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    by_s = np.argsort(s)
+    states = []
+    for n, layer in enumerate(int(l) for l in (by_s[-1], by_s[0], by_s[L // 3], by_s[2 * L // 3])):
+        cfg = synth.scaled(synth.CONFIGS["dsv3_long"], zipf_s=round(float(s[layer]), 3))
+        pop = synth.popularity(E, s[layer], idx, layer)
+        st = setup(cfg, dev, packed, e4m3, plan=plan, layer=layer, pop=pop, plan_ms=plan_ms,
+                   keep_host_weights=(n == 0))
+        if n > 0:
+            st["host_x"] = st["host_logits"] = None
+        log(f"stack layer {layer}: Zipf s={s[layer]:.2f}, {plan.layer(layer)['n_replicas']} replicas, heaviest rank "
+            f"{st['rank']}: {len(st['slots'])} slots, {int(st['rows'][st['rank']])} rows (mean {np.mean(st['rows']):.0f})")
+        states.append(st)
+    return states
 
 
 def lay_slots(st):
@@ -222,19 +264,20 @@ def bench_gate(args, name):
 
 
 def copy_calibration(args):
-    """A plain 256 MiB device-to-device copy: the known-size kernel against which the
-    FETCH_SIZE / WRITE_SIZE counters are scaled, and the box's own copy bandwidth."""
+    """A plain 256 MiB device-to-device copy (the library's craft_probe_copy): the known-size
+    kernel against which the FETCH_SIZE / WRITE_SIZE counters are scaled."""
     import torch
+    from paper_2603_28768_amd import binding
     n = 256 << 20
     a = torch.ones(n, dtype=torch.uint8, device="cuda")
     b = torch.empty_like(a)
     for _ in range(3):
-        b.copy_(a)
+        binding.probe_copy(a, b)
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     ev[0].record()
     for _ in range(args.steps):
-        b.copy_(a)
+        binding.probe_copy(a, b)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / args.steps
@@ -243,13 +286,12 @@ def copy_calibration(args):
 
 
 # HBM traffic of the gate/up kernel per launch from rocprofv3 counters (profiles/
-# rank_forward_qwen3_hbm_traffic.txt): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, scaled by
-# what the same counters read for a plain 256 MiB copy (x2.0 and x1.0).  The figure belongs to
-# the kernel as it was when the counters were taken: it is reported only while the sources
-# that shape that kernel still hash to the recorded value.
+# rank_forward_<workload>_hbm_traffic.txt): FETCH_SIZE and WRITE_SIZE in KiB per dispatch (mean
+# over the workload's launches), scaled by what the same counters read for a plain 256 MiB copy
+# (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
+# is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-TRAFFIC = {"qwen3": dict(fetch_kib=290167.5, write_kib=15123.5, fetch_scale=2.0, write_scale=1.0,
-                         sources_sha256="95adba5a15cf6f4dcabb3877139c07cc3937956fb3659b58d406aa29b71de099")}
+TRAFFIC = {}
 
 
 def kernel_sources_sha256():
@@ -266,6 +308,82 @@ def measured_traffic(cfg_name, packed):
     if t is None or not packed or t["sources_sha256"] != kernel_sources_sha256():
         return None
     return (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0
+
+
+def machine_rates(steps=10):
+    """This machine's own ceilings, measured with the library's probes on the current stream: a
+    plain 256 MiB copy (bytes read + written per second) and a register-only bf16 MFMA loop."""
+    import torch
+    from paper_2603_28768_amd import binding
+    n = 256 << 20
+    a = torch.ones(n, dtype=torch.uint8, device="cuda")
+    b = torch.empty_like(a)
+    sink = torch.empty(2 * 1024 * 256, dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for _ in range(3):
+        binding.probe_copy(a, b)
+        binding.probe_mfma_bf16(2000, sink)
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(steps):
+        binding.probe_copy(a, b)
+    ev[1].record()
+    ev[2].record()
+    flops = 0.0
+    for _ in range(steps):
+        flops += binding.probe_mfma_bf16(20000, sink)
+    ev[3].record()
+    torch.cuda.synchronize()
+    assert bool((b == 1).all())
+    return dict(copy_gbs=2.0 * n * steps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
+                mfma_bf16_tflops=flops / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e12)
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def ffn_work(st, wes):
+    """Algorithmic work of one state's expert FFN: per GEMM (bytes, flops), and the two bounds of
+    the pair over the rank's slots p with c_p rows: sum_p max(flops_p / MFMA peak, bytes_p / HBM
+    peak) (nothing overlaps between slots) and max(sum flops / peak, sum bytes / peak)."""
+    cfg = st["cfg"]
+    es = 2 if cfg.dtype == "bf16" else 4
+    H, I = cfg.H, cfg.I
+    M = int(st["rows"][st["rank"]])
+    live = sum(1 for r in st["slot_rows"] if r > 0)
+    flop_peak = (MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS) * 1e12
+    gu = (live * 2 * H * I * wes + M * H * es + M * I * es, 4.0 * H * I * M)
+    dn = (live * H * I * wes + M * I * es + M * H * es, 2.0 * H * I * M)
+    no_overlap = 0.0
+    for c in st["slot_rows"]:
+        if c > 0:
+            no_overlap += max(6.0 * H * I * c / flop_peak,
+                              (3 * H * I * wes + c * (2 * H + 2 * I) * es) / (HBM_PEAK_GBS * 1e9))
+    perfect = max((gu[1] + dn[1]) / flop_peak, (gu[0] + dn[0]) / (HBM_PEAK_GBS * 1e9))
+    return dict(M=M, live=live, gateup=gu, down=dn, no_overlap_s=no_overlap, perfect_overlap_s=perfect)
+
+
+def kernel_work(st, wes):
+    """Algorithmic (bytes, flops) per launch of every kernel of one state's forward."""
+    cfg = st["cfg"]
+    es = 2 if cfg.dtype == "bf16" else 4
+    f = ffn_work(st, wes)
+    A, S = cfg.T * cfg.k, len(lay_slots(st))
+    NB = (cfg.T + 31) // 32
+    M = f["M"]
+    return dict(route=(cfg.T * cfg.E * 4 + A * 9 + NB * cfg.E * 4, 0.0),
+                scan=(2 * NB * cfg.E * 4 + S * 16, 0.0),
+                dispatch=(A * 9 + A * 8, 0.0),
+                gateup=f["gateup"], down=f["down"],
+                combine=(M * cfg.H * es + cfg.T * cfg.H * es + A * 8, 0.0))
 
 
 def plan_curves(args):
@@ -301,10 +419,11 @@ def plan_curves(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="qwen3",
-                    help="tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only) | "
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="stack",
+                    help="stack (default: plan over 58 layers, four T=32768 layers executed) | "
+                         "tiny | qwen3 | dsv3 | kimi | dsv3_long | trace_load (histogram only) | "
                          "gate_qwen3 | gate_dsv3 | gate_kimi (gating network only) | "
                          "copy_calib (plain copy for counter calibration) | "
                          "plan_curves (host only: balancedness vs budget for the three planners)")
@@ -314,7 +433,8 @@ def main():
     ap.add_argument("--weights", default="bf16", choices=["bf16", "e4m3"],
                     help="storage of the packed expert weights: bf16, or E4M3 codes with a scale per row")
     ap.add_argument("--timing-level", type=int, default=1,
-                    help="1: HIP events around the gate/up GEMM; 2: around every kernel")
+                    help="inside the timed region: 1 = HIP events around the gate/up GEMM only, "
+                         "2 = around every kernel (a second, untimed pass always brackets every kernel)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU's share (the heaviest simulated rank); "
@@ -333,43 +453,67 @@ def main():
         return copy_calibration(args)
     if args.config.startswith("gate_"):
         return bench_gate(args, args.config[5:])
-    cfg = synth.CONFIGS[args.config]
     e4m3 = args.weights == "e4m3"
-    if e4m3:
-        assert cfg.dtype == "bf16" and not args.unpacked, "E4M3 weights go with the packed bf16 path"
-    st = setup(cfg, packed=not args.unpacked, e4m3=e4m3)
-    fwd, x, logits = st["fwd"], st["x"], st["logits"]
-    M = int(st["rows"][st["rank"]])
-    log(f"config {cfg.name}: T={cfg.T} H={cfg.H} I={cfg.I} E={cfg.E} k={cfg.k} D={cfg.D}; "
-        f"heaviest rank {st['rank']} holds {len(st['slots'])} slots, {M} rows "
-        f"(mean {np.mean(st['rows']):.0f}); plan {st['plan_ms']:.2f} ms")
+    packed = not args.unpacked
+    if args.config == "stack":
+        states = setup_stack(packed=packed, e4m3=e4m3)
+    else:
+        cfg = synth.CONFIGS[args.config]
+        if e4m3:
+            assert cfg.dtype == "bf16" and packed, "E4M3 weights go with the packed bf16 path"
+        states = [setup(cfg, packed=packed, e4m3=e4m3)]
+    cfg = states[0]["cfg"]
+    packed = packed and cfg.dtype == "bf16"
+    for st in states:
+        c = st["cfg"]
+        log(f"config {c.name} layer {st['layer']}: T={c.T} H={c.H} I={c.I} E={c.E} k={c.k} D={c.D}; "
+            f"heaviest rank {st['rank']} holds {len(st['slots'])} slots, {int(st['rows'][st['rank']])} rows "
+            f"(mean {np.mean(st['rows']):.0f}); plan {st['plan_ms']:.2f} ms; tiles {st['fwd'].tile_choice()}")
+
+    def one_step():
+        for st in states:
+            st["fwd"](st["x"], st["logits"])
 
     for _ in range(args.warmup):
-        fwd(x, logits)
+        one_step()
     torch.cuda.synchronize()
-    binding.timing_enable(args.timing_level, args.steps)
+    binding.timing_enable(args.timing_level, args.steps * len(states))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        fwd(x, logits)
+        one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     times = binding.timing_read()
     binding.timing_enable(0, 0)
-    rows, ovf = fwd.result()
-    assert ovf == 0 and rows == M, (rows, M, ovf)
+    for st in states:
+        rows, ovf = st["fwd"].result()
+        assert ovf == 0 and rows == int(st["rows"][st["rank"]]), (rows, ovf)
+    # a second, short pass with every kernel bracketed by events (outside the timed region: the
+    # events between kernels cost a few microseconds each)
+    side_steps = max(3, min(20, args.steps))
+    binding.timing_enable(2, side_steps * len(states))
+    for _ in range(side_steps):
+        one_step()
+    torch.cuda.synchronize()
+    all_times = binding.timing_read()
+    binding.timing_enable(0, 0)
+    rates = machine_rates()
 
     ms_step = dt / args.steps * 1e3
-    es = 2 if cfg.dtype == "bf16" else 4
-    live = sum(1 for r in st["slot_rows"] if r > 0)
+    wes = 1 if e4m3 else (2 if cfg.dtype == "bf16" else 4)        # bytes per stored weight
+    work = [ffn_work(st, wes) for st in states]
+    n_l = len(states)
+    tokens = sum(st["cfg"].T for st in states)
+    M_all = sum(w["M"] for w in work)
+    # dominant kernel: the grouped gate/up GEMM; work per launch = mean over the executed layers
     gu_ms = times["gateup"]["ms"] / max(times["gateup"]["launches"], 1)
-    wes = 1 if e4m3 else es                           # bytes per stored weight
-    gu_bytes = live * 2 * cfg.H * cfg.I * wes + M * cfg.H * es + M * cfg.I * es
-    gu_flops = 4.0 * cfg.H * cfg.I * M
+    gu_bytes = sum(w["gateup"][0] for w in work) / n_l
+    gu_flops = sum(w["gateup"][1] for w in work) / n_l
     gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
     tfs = gu_flops / (gu_ms * 1e-3) / 1e12
     flop_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
-    traffic = measured_traffic(cfg.name, not args.unpacked and cfg.dtype == "bf16" and not e4m3)   # bytes per launch
+    traffic = measured_traffic(args.config, packed and not e4m3)             # bytes per launch
     t_hbm, t_mfma = gu_bytes / (HBM_PEAK_GBS * 1e9), gu_flops / (flop_peak * 1e12)
     if t_hbm >= t_mfma:
         roof = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
@@ -381,36 +525,68 @@ def main():
                 launches=times["gateup"]["launches"], algorithmic_bytes=gu_bytes,
                 algorithmic_flops=gu_flops, hbm_frac=gbs / HBM_PEAK_GBS, flop_frac=tfs / flop_peak,
                 achieved_gbs=gbs, achieved_tflops=tfs)
+    # every kernel of the forward from the second pass: mean duration per launch, algorithmic
+    # bytes (and flops) per launch, fractions of the published peaks
+    kms = {k: v["ms"] / max(v["launches"], 1) for k, v in all_times.items() if v["launches"]}
+    per = [kernel_work(st, wes) for st in states]
+    kernels = {}
+    for name in ("route", "scan", "dispatch", "gateup", "down", "combine"):
+        if name not in kms:
+            continue
+        b = sum(p_[name][0] for p_ in per) / n_l
+        f = sum(p_[name][1] for p_ in per) / n_l
+        d = dict(ms=kms[name], algorithmic_bytes=b, gbs=b / (kms[name] * 1e-3) / 1e9)
+        d["hbm_frac"] = d["gbs"] / HBM_PEAK_GBS
+        if f:
+            d["tflops"] = f / (kms[name] * 1e-3) / 1e12
+            d["flop_frac"] = d["tflops"] / flop_peak
+        kernels[name] = d
+    ffn_ms = kms.get("gateup", 0.0) + kms.get("down", 0.0)
+    no_ov = sum(w["no_overlap_s"] for w in work) / n_l * 1e3
+    perfect = sum(w["perfect_overlap_s"] for w in work) / n_l * 1e3
+    roof.update(kernels=kernels,
+                ffn_bounds=dict(what="gate/up + down of one layer's rank share against the published peaks: "
+                                     "sum over slots of max(6HI c_p / MFMA peak, (3HI + c_p(2H+2I)) es / HBM peak), "
+                                     "and max(sum flops / peak, sum bytes / peak)",
+                                no_overlap_ms=no_ov, perfect_overlap_ms=perfect, measured_ms=ffn_ms,
+                                frac_of_no_overlap=no_ov / ffn_ms if ffn_ms else None,
+                                frac_of_perfect_overlap=perfect / ffn_ms if ffn_ms else None),
+                machine=dict(copy_gbs=rates["copy_gbs"], mfma_bf16_tflops=rates["mfma_bf16_tflops"],
+                             frac_of_measured_copy=gbs / rates["copy_gbs"],
+                             frac_of_measured_mfma=tfs / rates["mfma_bf16_tflops"],
+                             what="craft_probe_copy of 256 MiB (bytes read + written per second) and "
+                                  "craft_probe_mfma_bf16 (register-only v_mfma_f32_32x32x16_bf16 loop) on this GPU"))
 
-    out = dict(metric="MoE rank-forward tokens/s on 1 GPU", value=cfg.T / (ms_step * 1e-3),
+    if len(states) == 1:
+        workload = (f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} I={cfg.I} Zipf s={cfg.zipf_s}, "
+                    f"{cfg.D} simulated ranks, {cfg.replica_slots} replica slots; heaviest rank's share")
+    else:
+        workload = (f"stack: routing traces of 58 layers x 256 experts (Zipf s in [0.6,1.6]) -> GPU histogram -> "
+                    f"plan at 256 replicas over {cfg.D} simulated ranks; {n_l} executed layers "
+                    f"(T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} I={cfg.I}) each under its own layer's plan; "
+                    f"heaviest rank's share of every layer; a step is all {n_l} layers, tokens/s counts "
+                    f"T per layer")
+    out = dict(metric="MoE rank-forward tokens/s on 1 GPU", value=tokens / (ms_step * 1e-3),
                unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=ms_step, higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype=cfg.dtype, data="synthetic",
-               config=dict(workload=f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} "
-                                    f"I={cfg.I} Zipf s={cfg.zipf_s}, {cfg.D} simulated ranks, "
-                                    f"{cfg.replica_slots} replica slots; heaviest rank's share",
-                           rank=int(st["rank"]), rank_slots=len(st["slots"]), rank_rows=M,
-                           rows_per_s=M / (ms_step * 1e-3), plan_ms=st["plan_ms"],
+               config=dict(workload=workload,
+                           layers=[dict(layer=int(st["layer"]), zipf_s=st["cfg"].zipf_s, rank=int(st["rank"]),
+                                        rank_slots=len(st["slots"]), rank_rows=w["M"],
+                                        replicas=int(st["lay"]["n_replicas"]),
+                                        tiles=list(st["fwd"].tile_choice()),
+                                        balancedness_realized=float(np.mean(st["rows"]) / np.max(st["rows"])))
+                                   for st, w in zip(states, work)],
+                           rank_rows=M_all, rows_per_s=M_all / (ms_step * 1e-3), plan_ms=states[0]["plan_ms"],
                            weights=("E4M3 codes + row scales, packed at load" if e4m3 else "packed at load")
-                           if (not args.unpacked and cfg.dtype == "bf16") else "row-major",
-                           balancedness_realized=float(np.mean(st["rows"]) / np.max(st["rows"]))),
+                           if packed else "row-major"),
                roofline=roof)
-    if args.timing_level == 2:
-        out["kernel_ms"] = {k: v["ms"] / max(v["launches"], 1) for k, v in times.items()}
-        # algorithmic bytes (and FLOPs of the two GEMMs) per launch of every kernel of the forward
-        A, S = cfg.T * cfg.k, len(lay_slots(st))
-        NB = (cfg.T + 31) // 32
-        alg = dict(route=(cfg.T * cfg.E * 4 + A * 9 + NB * cfg.E * 4, 0.0),
-                   scan=(2 * NB * cfg.E * 4 + S * 16, 0.0),
-                   dispatch=(A * 9 + A * 8, 0.0),
-                   gateup=(gu_bytes, gu_flops),
-                   down=(live * cfg.H * cfg.I * wes + M * cfg.I * es + M * cfg.H * es, 2.0 * cfg.H * cfg.I * M),
-                   combine=(M * cfg.H * es + cfg.T * cfg.H * es + A * 8, 0.0))
-        out["kernels"] = {k: dict(ms=out["kernel_ms"][k], algorithmic_bytes=b, gbs=b / (out["kernel_ms"][k] * 1e-3) / 1e9,
-                                  **({"tflops": f / (out["kernel_ms"][k] * 1e-3) / 1e12} if f else {}))
-                          for k, (b, f) in alg.items() if out["kernel_ms"].get(k, 0) > 0}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, st)
+        base = cpu_baseline(states[0]["cfg"], states[0])
+        base["cpu_model"] = cpu_model()
+        if n_l > 1:
+            base["sample"] = f"layer {states[0]['layer']} of the {n_l} executed layers: " + base["sample"]
+        out["cpu_baseline"] = base
     print(json.dumps(out), flush=True)
 
 

@@ -15,7 +15,8 @@
  *   - `stream` arguments are hipStream_t values passed as void* (NULL = the null stream).
  *     Device entry points only enqueue work: they return after launching, do not
  *     synchronise, and report launch-time errors as CRAFT_EHIP.  Faults inside a kernel
- *     surface at the caller's next synchronisation.
+ *     surface at the caller's next synchronisation.  The two exceptions say so below:
+ *     craft_moe_rank_forward_result and craft_timing_read wait for what they read.
  *   - Every call returns a craft_status; nothing is thrown across the boundary.
  *   - Router scores must be finite (NaN is not detected; the result is then unspecified).
  *   - Row-major everywhere; [a][b] means b is contiguous.
@@ -36,7 +37,7 @@ typedef enum {
     CRAFT_ENOMEM = -2,      /* host allocation failed */
     CRAFT_EHIP = -3,        /* a HIP runtime call or kernel launch failed */
     CRAFT_EWORKSPACE = -4,  /* workspace or table buffer too small */
-    CRAFT_EINFEASIBLE = -5  /* the request cannot be met (e.g. more replicas than E*(D-1)) */
+    CRAFT_EINFEASIBLE = -5  /* the request exceeds a fixed limit of the library */
 } craft_status;
 
 const char *craft_status_str(craft_status s);
@@ -45,8 +46,8 @@ const char *craft_status_str(craft_status s);
 enum { CRAFT_F32 = 0, CRAFT_BF16 = 1 };
 
 /* -------------------------------------------------------------- gating network
- * Sec. 2.1: for each token the gating network computes a score for each expert.  The paper
- * gives the network no form; this is the usual linear gate without bias,
+ * Sec. 2.1 (routing): expert scores per token come from a gating network whose form the paper
+ * leaves open; this is the usual linear gate without bias,
  *   logits[t][e] = sum_h x[t][h] * w_router[e][h]   (fp32 accumulation, fp32 result).
  *   dtype     CRAFT_F32 or CRAFT_BF16: element type of x and w_router
  *   x         DEVICE [T][H], 16-byte aligned
@@ -71,8 +72,9 @@ craft_status craft_router_logits(int32_t dtype, const void *x, const void *w_rou
                                  size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------ routing
- * Sec. 2.1: the gating network's scores select the top-K experts of each token.
- *   logits  DEVICE [T][E] fp32 router scores
+ * Sec. 2.1 (routing): each token activates the K experts it scores highest.
+ *   logits  DEVICE [T][E] fp32 router scores, 4-byte aligned (rows are read 16 bytes at a time
+ *           when the base is 16-byte aligned and E % 4 == 0, one score at a time otherwise)
  *   ids     DEVICE [T][k] int32: expert with the (j+1)-th largest score (equal scores:
  *           lower expert id first)
  *   w       DEVICE [T][k] fp32: softmax probability of that expert over all E scores;
@@ -83,8 +85,8 @@ craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t
                               int32_t renormalize, int32_t *ids, float *w, void *stream);
 
 /* ------------------------------------------------------------- load profiling
- * Sec. 3.1: expert load = tokens dispatched to an expert after routing, recorded over
- * batch x layer x expert (the W of Alg. 1).
+ * Sec. 3.1 "expert load", the W[B][L][E] input of Alg. 1: how many routed assignments name
+ * each expert, per profiling batch and layer.
  *   topk_ids      DEVICE [L][T][k] int32 routing trace; every id must lie in [0, E):
  *                 ids outside are not counted and make the call's result unspecified
  *   batch_tokens  tokens per profiling batch; B = ceil(T / batch_tokens)
@@ -199,8 +201,10 @@ craft_status craft_plan_diff(const craft_plan_t *old_plan, const craft_plan_t *n
 /* Device copy of the tables one rank's forward needs.  Query the size, let the caller
  * allocate DEVICE memory (256-byte aligned), upload once, and pass the pointer to every
  * forward of that (plan, layer, rank).  The plan remembers which buffers it filled; a
- * forward given any other pointer returns CRAFT_EINVAL.  The upload is enqueued on
- * `stream` from pageable host memory owned by the plan. */
+ * forward given any other pointer returns CRAFT_EINVAL.  The copy is enqueued on `stream`
+ * (no synchronisation) from pageable host memory that belongs to the plan, so the plan has to
+ * outlive it; a forward enqueued later on the same stream sees the tables.  A buffer may be
+ * filled again, also for another (layer, rank): it then counts for the last one only. */
 craft_status craft_plan_tables_bytes(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                      size_t *bytes);
 craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,
@@ -264,7 +268,8 @@ craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_c
  *                 w[t][j] * Y[row of (t,j)]; tokens with none get zeros
  *
  *   x        DEVICE [T][H] activations, dtype
- *   logits   DEVICE [T][E] fp32 router scores, or NULL: then the forward computes them first,
+ *   logits   DEVICE [T][E] fp32 router scores (aligned as for craft_route_topk), or NULL: then
+ *            the forward computes them first,
  *            as craft_router_logits does (with its workspace), from
  *   w_router DEVICE [E][H] gate weights, dtype (ignored when logits is given)
  *   w_gate, w_up  DEVICE arrays of s device pointers, one per slot of this rank in slot
@@ -348,7 +353,8 @@ craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t laye
 
 /* After the caller has synchronised the stream: what the last forward on this workspace
  * found.  rows = rows routed to the rank; overflow != 0 when rows > max_rows (nothing was
- * computed).  Copies 16 bytes from the device, synchronously. */
+ * computed).  Copies 16 bytes from the device with a blocking copy on the null stream: this
+ * call synchronises, and must not be made while a stream is capturing. */
 craft_status craft_moe_rank_forward_result(const void *workspace, int64_t *rows,
                                            int32_t *overflow);
 
@@ -371,6 +377,20 @@ enum {
 };
 craft_status craft_timing_enable(int32_t level, int32_t max_forwards);
 craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_K_COUNT]);
+
+/* ------------------------------------------------------------ measurement probes
+ * Not part of the method: two kernels of known work, so that a benchmark can report this
+ * machine's own ceilings next to the published ones and scale memory counters.
+ * craft_probe_copy: dst[i] = src[i] for `bytes` bytes (a multiple of 16; both DEVICE, 16-byte
+ *   aligned, not overlapping): reads `bytes` and writes `bytes`, nothing else.
+ * craft_probe_mfma_bf16: blocks x 4 wavefronts each issue iters x 4 independent
+ *   v_mfma_f32_32x32x16_bf16 on register operands (no memory traffic but the final store of one
+ *   float per thread to sink, DEVICE [blocks * 256]); *flops = the floating-point operations
+ *   the launch performs (2 * 32 * 32 * 16 per MFMA).  blocks = 0: two per compute unit.
+ * Both only enqueue on `stream`; time them with events on that stream. */
+craft_status craft_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, double *flops,
+                                   void *stream);
 
 #ifdef __cplusplus
 }

@@ -74,6 +74,8 @@ EXPORTS = {
     "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32),
                                                     P(c_i32), P(c_i32)]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
+    "craft_probe_copy": (ctypes.c_int, [c_vp, c_vp, c_i64, c_vp]),
+    "craft_probe_mfma_bf16": (ctypes.c_int, [c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
     "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
     "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
 }
@@ -448,6 +450,21 @@ class RankForward:
         _check(lib().craft_moe_rank_forward_result(_dev(self.workspace), rows, ovf),
                "craft_moe_rank_forward_result")
         return rows.value, ovf.value
+
+
+def probe_copy(src, dst, stream=None):
+    """dst <- src (device uint8 tensors of equal size, a multiple of 16 bytes)."""
+    assert src.numel() == dst.numel() and src.element_size() == dst.element_size() == 1
+    _check(lib().craft_probe_copy(_dev(src), _dev(dst), src.numel(), _stream_ptr(stream)), "craft_probe_copy")
+
+
+def probe_mfma_bf16(iters: int, sink, blocks: int = 0, stream=None) -> float:
+    """Enqueue the register-only MFMA loop; returns the floating-point operations it performs.
+    sink: device float32 tensor with at least blocks * 256 elements (blocks = 0: 2 per CU)."""
+    fl = ctypes.c_double()
+    _check(lib().craft_probe_mfma_bf16(blocks, iters, _dev(sink), fl, _stream_ptr(stream)),
+           "craft_probe_mfma_bf16")
+    return fl.value
 
 
 def timing_enable(level: int, max_forwards: int = 0):

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libcraft.so")
 
-SOURCES = ["planner.cpp", "forward.cpp", "route.hip", "router.hip", "dispatch.hip", "load.hip", "ffn.hip", "ffn_packed.hip", "quant.hip",
+SOURCES = ["planner.cpp", "forward.cpp", "route.hip", "router.hip", "dispatch.hip", "load.hip", "ffn.hip", "ffn_packed.hip", "quant.hip", "probe.hip",
            "combine.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -1,5 +1,5 @@
-// Gather-weighted combine (Sec. 2.1: the activated experts' outputs are aggregated into a
-// weighted sum).  One 64-lane wavefront per token; a lane owns 16-byte column chunks of the
+// Gather-weighted combine: the last step of the MoE layer of Sec. 2.1, each token's sum of
+// its experts' outputs scaled by the routing weights.  One 64-lane wavefront per token; a lane owns 16-byte column chunks of the
 // row.  Only assignments whose dispatched position falls inside this rank's row range
 // contribute, added in ascending j with fp32 accumulation; there are no atomics, so the
 // result does not depend on scheduling.  Tokens with no assignment on the rank get zeros.

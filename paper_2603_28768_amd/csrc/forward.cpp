@@ -1,5 +1,6 @@
 // Device-side entry points of the C ABI: argument checks, workspace layout, launches.
 #include <algorithm>
+#include <atomic>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -155,7 +156,7 @@ double ffn_makespan(const std::vector<double> &slot_rows, int32_t frags, bool ev
     return end;
 }
 
-using tile_choice = craft_plan_t::tile_choice;
+struct tile_choice { int32_t frags[2]; bool riders[2]; };
 
 tile_choice choose_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank, int64_t T, int32_t k,
                          int32_t H, int32_t I, int32_t cus) {
@@ -206,18 +207,32 @@ tile_choice choose_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank, 
     return best;
 }
 
+// The choice for (layer, rank, T, k, H, I) is made once and kept with the plan: later forwards
+// of the same shape find it by walking a short insert-only list, without a lock.
 tile_choice tiles_for(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a,
                       bool packed) {
     if (a->dtype != CRAFT_BF16) return {{kFragsF32, kFragsF32}, {false, false}};
     if (!packed) return {{kFragsBf16, kFragsBf16}, {false, false}};
-    craft_plan_t *p = const_cast<craft_plan_t *>(plan);
-    const std::array<int64_t, 6> key{layer, rank, a->T, a->k, a->H, a->I};
-    std::lock_guard<std::mutex> lk(p->reg_mutex);
-    auto it = p->tile_cache.find(key);
-    if (it == p->tile_cache.end())
-        it = p->tile_cache.emplace(key, choose_tiles(plan, layer, rank, a->T, a->k, a->H, a->I,
-                                                     cached_num_cu())).first;
-    tile_choice c = it->second;
+    craft_rank_state &rs = plan->state(layer, rank);
+    auto find = [&]() -> const craft_tile_choice * {
+        for (const craft_tile_choice *t = rs.tiles.load(std::memory_order_acquire); t; t = t->next)
+            if (t->T == a->T && t->k == a->k && t->H == a->H && t->I == a->I) return t;
+        return nullptr;
+    };
+    const craft_tile_choice *hit = find();
+    if (!hit) {
+        std::lock_guard<std::mutex> lk(rs.mu);
+        hit = find();
+        if (!hit) {
+            const tile_choice c = choose_tiles(plan, layer, rank, a->T, a->k, a->H, a->I, cached_num_cu());
+            craft_tile_choice *n = new craft_tile_choice{a->T, a->k, a->H, a->I, {c.frags[0], c.frags[1]},
+                                                         {c.riders[0], c.riders[1]},
+                                                         rs.tiles.load(std::memory_order_relaxed)};
+            rs.tiles.store(n, std::memory_order_release);
+            hit = n;
+        }
+    }
+    tile_choice c{{hit->frags[0], hit->frags[1]}, {hit->riders[0], hit->riders[1]}};
     // the caller's own heights: riders wherever such tiles can carry them, unless told
     const int32_t rows_arg[2] = {a->tile_rows_gateup, a->tile_rows_down};
     const int32_t riders_arg[2] = {a->riders_gateup, a->riders_down};
@@ -282,7 +297,7 @@ craft_status craft_route_topk(const float *logits, int64_t T, int32_t E, int32_t
                               int32_t renormalize, int32_t *ids, float *w, void *stream) {
     if (T < 0 || E <= 0 || E > 1024 || k <= 0 || k > E || k > 64) return CRAFT_EINVAL;
     if (T == 0) return CRAFT_OK;
-    if (!logits || !ids || !w) return CRAFT_EINVAL;
+    if (!logits || !ids || !w || !aligned(logits, 4) || !aligned(ids, 4) || !aligned(w, 4)) return CRAFT_EINVAL;
     RouteArgs ra{logits, T, E, k, renormalize ? 1 : 0, ids, w, nullptr, nullptr, nullptr};
     return launch_route(ra, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
@@ -312,17 +327,34 @@ craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t
     const craft_layer_plan &lp = plan->layers[layer];
     const size_t words = craft_tables_words(plan->E, (int32_t)lp.slot_expert.size());
     if (bytes < words * sizeof(int32_t)) return CRAFT_EWORKSPACE;
-    std::vector<int32_t> host(words);
-    craft_tables_build(lp, plan->E, rank, host.data());
-    // the staging vector dies with this call, so the copy has to be complete on return
-    if (hipMemcpyAsync(dev_tables, host.data(), words * sizeof(int32_t), hipMemcpyHostToDevice,
-                       as_stream(stream)) != hipSuccess)
-        return CRAFT_EHIP;
-    if (hipStreamSynchronize(as_stream(stream)) != hipSuccess) return CRAFT_EHIP;
-    std::lock_guard<std::mutex> lk(plan->reg_mutex);
-    for (auto &r : plan->regs)
-        if (r.dev == dev_tables) { r.layer = layer; r.rank = rank; return CRAFT_OK; }
-    plan->regs.push_back({dev_tables, layer, rank});
+    craft_rank_state &rs = plan->state(layer, rank);
+    try {
+        {
+            // the host copy of the tables is built once and stays with the plan, so the copy
+            // below may still be in flight when this call returns
+            std::lock_guard<std::mutex> lk(rs.mu);
+            if (rs.host_tables.empty()) {
+                std::vector<int32_t> host(words);
+                craft_tables_build(lp, plan->E, rank, host.data());
+                rs.host_tables.swap(host);
+            }
+        }
+        std::lock_guard<std::mutex> lk(plan->reg_mutex);
+        auto it = plan->reg_of.find(dev_tables);
+        if (it != plan->reg_of.end()) {
+            // the buffer held another rank's tables (or these): its old entry goes blank
+            it->second->dev.store(nullptr, std::memory_order_release);
+            plan->reg_of.erase(it);
+        }
+        if (hipMemcpyAsync(dev_tables, rs.host_tables.data(), words * sizeof(int32_t), hipMemcpyHostToDevice,
+                           as_stream(stream)) != hipSuccess)
+            return CRAFT_EHIP;
+        craft_table_reg *n = new craft_table_reg{{dev_tables}, rs.regs.load(std::memory_order_relaxed)};
+        rs.regs.store(n, std::memory_order_release);
+        plan->reg_of.emplace(dev_tables, n);
+    } catch (const std::bad_alloc &) {
+        return CRAFT_ENOMEM;
+    }
     return CRAFT_OK;
 }
 
@@ -393,17 +425,20 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
     return CRAFT_OK;
 }
 
-craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
-                                    const craft_fwd_args *a, void *stream) {
-    craft_status st = check_fwd(plan, layer, rank, a);
-    if (st != CRAFT_OK) return st;
-    if (!a->workspace || !aligned(a->workspace, 256) || !a->tables) return CRAFT_EINVAL;
+}  // extern "C"
+
+namespace {
+
+// One forward on `workspace`; `a` has passed check_fwd.
+craft_status forward_on(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+    if (!workspace || !aligned(workspace, 256) || !a->tables) return CRAFT_EINVAL;
     {
-        craft_plan_t *p = const_cast<craft_plan_t *>(plan);
-        std::lock_guard<std::mutex> lk(p->reg_mutex);
+        // the tables must be a buffer this plan filled for this (layer, rank)
         bool known = false;
-        for (auto &r : p->regs)
-            known = known || (r.dev == a->tables && r.layer == layer && r.rank == rank);
+        for (const craft_table_reg *r = plan->state(layer, rank).regs.load(std::memory_order_acquire); r && !known;
+             r = r->next)
+            known = r->dev.load(std::memory_order_relaxed) == a->tables;
         if (!known) return CRAFT_EINVAL;
     }
     const craft_layer_plan &lp = plan->layers[layer];
@@ -412,7 +447,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     const int32_t nslots = s_hi - s_lo;
     const bool own_gate = a->logits == nullptr;
     Layout L = make_layout(a->T, a->k, E, S, nslots, a->H, a->I, a->dtype, a->max_rows, own_gate);
-    if (a->workspace_bytes < L.total) return CRAFT_EWORKSPACE;
+    if (workspace_bytes < L.total) return CRAFT_EWORKSPACE;
     if (a->T > 0) {
         if (!a->x || !a->out || (own_gate && !a->w_router)) return CRAFT_EINVAL;
         if (!aligned(a->x, 16) || !aligned(a->out, 16)) return CRAFT_EINVAL;
@@ -429,7 +464,7 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
             return CRAFT_EINVAL;
     }
     hipStream_t s = as_stream(stream);
-    unsigned char *ws = static_cast<unsigned char *>(a->workspace);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
     int32_t *ctrl = reinterpret_cast<int32_t *>(ws + L.ctrl);
     int32_t *ids = reinterpret_cast<int32_t *>(ws + L.ids);
     float *w = reinterpret_cast<float *>(ws + L.w);
@@ -509,6 +544,17 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     return CRAFT_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                    const craft_fwd_args *a, void *stream) {
+    craft_status st = check_fwd(plan, layer, rank, a);
+    if (st != CRAFT_OK) return st;
+    return forward_on(plan, layer, rank, a, a->workspace, a->workspace_bytes, stream);
+}
+
 craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                           const craft_fwd_args *a, int32_t *rows_gateup,
                                           int32_t *rows_down, int32_t *riders_gateup,
@@ -531,6 +577,21 @@ craft_status craft_moe_rank_forward_result(const void *workspace, int64_t *rows,
     if (rows) *rows = ctrl[CTRL_ROWS];
     if (overflow) *overflow = ctrl[CTRL_OVERFLOW];
     return CRAFT_OK;
+}
+
+craft_status craft_probe_copy(const void *src, void *dst, int64_t bytes, void *stream) {
+    if (bytes < 0 || bytes % 16) return CRAFT_EINVAL;
+    if (bytes == 0) return CRAFT_OK;
+    if (!src || !dst || !aligned(src, 16) || !aligned(dst, 16)) return CRAFT_EINVAL;
+    return launch_probe_copy(src, dst, bytes, cached_num_cu(), as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                                 : CRAFT_EHIP;
+}
+
+craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, double *flops, void *stream) {
+    if (blocks < 0 || blocks > (1 << 20) || iters <= 0 || !sink || !aligned(sink, 4)) return CRAFT_EINVAL;
+    if (blocks == 0) blocks = 2 * cached_num_cu();
+    if (flops) *flops = (double)blocks * 4.0 * (double)iters * 4.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return launch_probe_mfma(blocks, iters, sink, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
 
 craft_status craft_timing_enable(int32_t level, int32_t max_forwards) {

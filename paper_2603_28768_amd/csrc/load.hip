@@ -1,5 +1,5 @@
-// Expert-load histogram over routing traces (Sec. 3.1: expert load = tokens dispatched to
-// an expert after routing; recorded per batch, layer and expert -- the W of Alg. 1).
+// Expert-load histogram over routing traces: the W[B][L][E] that Alg. 1 takes as input
+// (Sec. 3.1 "expert load"), counted per profiling batch, layer and expert.
 //
 // HBM-bound: 4 bytes read per assignment, output negligible.  A workgroup streams one
 // chunk of one (batch, layer) cell with 16-byte loads and counts into LDS.  Every wave

@@ -281,7 +281,6 @@ void craft_tables_build(const craft_layer_plan &lp, int32_t E, int32_t rank, int
     const int32_t S = (int32_t)lp.slot_expert.size();
     craft_tables_header h;
     std::memset(&h, 0, sizeof(h));
-    h.magic = CRAFT_TABLES_MAGIC;
     h.E = E;
     h.S = S;
     h.s_lo = lp.rank_slot_off[rank];
@@ -319,7 +318,7 @@ const char *craft_status_str(craft_status s) {
         case CRAFT_ENOMEM: return "out of host memory";
         case CRAFT_EHIP: return "HIP runtime error";
         case CRAFT_EWORKSPACE: return "workspace too small";
-        case CRAFT_EINFEASIBLE: return "infeasible request";
+        case CRAFT_EINFEASIBLE: return "request exceeds a fixed limit of the library";
     }
     return "unknown status";
 }
@@ -354,6 +353,7 @@ craft_status craft_plan(const craft_plan_params *pp, craft_plan_t **out) {
 
         std::unique_ptr<struct craft_plan> plan(new struct craft_plan());
         plan->L = L; plan->E = E; plan->D = D; plan->gpus_per_node = pp->gpus_per_node;
+        plan->ranks.reset(new craft_rank_state[(size_t)L * D]);
 
         std::vector<std::vector<int32_t>> copies(L, std::vector<int32_t>(E, 1));
         std::vector<int32_t> x(L, 0);

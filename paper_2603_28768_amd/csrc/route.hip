@@ -1,5 +1,4 @@
-// Router softmax / top-k (Sec. 2.1: the gating network scores every expert and the
-// top-K scores are activated).
+// Router softmax / top-k: the top-K routing step of the MoE layer of Sec. 2.1.
 //
 // A token is handled by one 16-lane DPP row of a 64-lane wavefront, so a wave routes four
 // tokens at once and every cross-lane step is a row-local DPP move (quad permutes and
@@ -60,7 +59,8 @@ __global__ __launch_bounds__(kThreads) void route_kernel(RouteArgs a) {
     const int tid = threadIdx.x;
     const int sub = tid & 15;                      // lane inside the token's row
     const bool ranks = a.hist != nullptr;
-    const bool vec_ok = (a.E & 3) == 0;            // rows 16-byte aligned
+    // 16-byte loads need every row 16-byte aligned; otherwise the scores are read one by one
+    const bool vec_ok = (a.E & 3) == 0 && (reinterpret_cast<uintptr_t>(a.logits) & 15) == 0;
 
     if (ranks) {
         for (int e = tid; e < a.E; e += kThreads) mask[e] = 0u;

@@ -1,5 +1,5 @@
-// Gating-network scores (Sec. 2.1: for each token the gating network computes a score for
-// each expert).  The paper gives no form for the network; this is the usual linear gate,
+// Gating-network scores, the input of top-K routing (Sec. 2.1).  The paper leaves the form of
+// the network open; this is the usual linear gate,
 //   logits[t][e] = sum_h x[t][h] * Wr[e][h],
 // both operands contiguous along the contraction, fp32 accumulation, fp32 scores.  The top-k
 // step consumes these scores exactly as it consumes scores handed in from outside.

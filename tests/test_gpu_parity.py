@@ -2,8 +2,6 @@
 seeded inputs.  Integer results (ids, counts, dispatch indices) are compared bit for bit;
 gate weights to 1e-5 relative; the layer output to max|gpu-ref| <= tol * max|ref| with
 tol = 1e-2 for bf16 storage (fp32 accumulation) and 1e-4 for fp32 storage."""
-import ctypes
-import os
 
 import numpy as np
 import pytest
@@ -16,16 +14,6 @@ from cases import Case
 pytestmark = pytest.mark.gpu
 
 TOL = {"bf16": 1e-2, "f32": 1e-4}
-
-
-@pytest.fixture(scope="module")
-def torch_cuda():
-    import torch
-    if not torch.cuda.is_available():
-        pytest.fail("GPU tests need a GPU")
-    assert os.path.exists(binding.LIB_PATH), "libcraft.so has not been built"
-    binding.lib()
-    return torch
 
 
 def _np(t):
@@ -201,14 +189,87 @@ def test_forward_with_its_own_gating_network(torch_cuda, dtype, T, H, I, E, k, D
 
 # --------------------------------------------------------------------- forward
 
-def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False, knobs=None):
+def _row_units(case: Case, rank: int, heights):
+    """Row ranges [a, b) (positions in the rank's row block) of everything the packed FFN
+    schedules as a unit, for both ways a busy slot's fragments may be cut into row-tiles of the
+    given heights (full tiles and a remainder, or shared evenly): the first and the last 32-row
+    fragment of every row-tile of every slot with more than 64 rows, and every 32-row fragment
+    of the slots with at most 64 rows (a tile of their own or a rider on a busy tile)."""
+    p_lo, p_hi = case.rank_slot_off[rank], case.rank_slot_off[rank + 1]
+    lo = int(case.slot_off[p_lo])
+    units = []
+    for p in range(p_lo, p_hi):
+        a, n = int(case.slot_off[p]) - lo, int(case.slot_cnt[p])
+        F = (n + 31) // 32
+        if n == 0:
+            continue
+        if n <= 64:
+            units += [(a + 32 * f, a + min(32 * f + 32, n)) for f in range(F)]
+            continue
+        for h in heights:
+            f = h // 32
+            m = (F + f - 1) // f
+            for cut in ([min(i * f, F) for i in range(m + 1)], [i * F // m for i in range(m + 1)]):
+                for f0, f1 in zip(cut[:-1], cut[1:]):
+                    units.append((a + 32 * f0, a + min(32 * f0 + 32, n)))
+                    units.append((a + 32 * (f1 - 1), a + min(32 * f1, n)))
+    return units
+
+
+def _assert_units_compared(case: Case, rank: int, tokens, heights):
+    """Every unit of the FFN's work on this rank has at least one row whose token is among the
+    compared ones (all tokens when `tokens` is None)."""
+    cfg = case.cfg
+    p_lo, p_hi = case.rank_slot_off[rank], case.rank_slot_off[rank + 1]
+    lo, hi = int(case.slot_off[p_lo]), int(case.slot_off[p_hi])
+    seen = np.zeros(hi - lo, dtype=bool)
+    d = case.dest.reshape(cfg.T, cfg.k)
+    d = d if tokens is None else d[np.asarray(tokens)]
+    d = d[(d >= lo) & (d < hi)]
+    seen[d - lo] = True
+    units = _row_units(case, rank, heights)
+    missed = [u for u in units if not seen[u[0]:u[1]].any()]
+    assert units and not missed, missed[:5]
+    return len(units)
+
+
+def _tokens_covering_units(case: Case, rank: int, heights, extra: int = 0):
+    """A token for the first and for the last row of every unit (see _row_units), a few tokens
+    with no row on the rank, and `extra` random ones."""
+    cfg = case.cfg
+    lo = int(case.slot_off[case.rank_slot_off[rank]])
+    hi = int(case.slot_off[case.rank_slot_off[rank + 1]])
+    toks = set()
+    for a, b in _row_units(case, rank, heights):
+        toks.add(int(case.src[lo + a]) // cfg.k)
+        toks.add(int(case.src[lo + b - 1]) // cfg.k)
+    d = case.dest.reshape(cfg.T, cfg.k)
+    off = np.nonzero(~((d >= lo) & (d < hi)).any(1))[0]
+    toks.update(int(t) for t in off[:2])
+    if extra:
+        toks.update(int(t) for t in np.random.default_rng(1).choice(cfg.T, size=extra, replace=False))
+    return sorted(toks)
+
+
+def _check_rank(torch, case: Case, rank: int, tokens=None, max_rows=0, packed=False, knobs=None, ref=None,
+                cover=False):
+    """One forward of `rank` through the C ABI against the checker: integer results everywhere,
+    the output on `tokens` (None: every token).  `ref`: a checker result for the same rank and
+    tokens computed earlier.  `cover`: also assert that the compared tokens reach every
+    row-tile, cold slot and rider unit of the two grouped GEMMs as this launch cuts them."""
     cfg = case.cfg
     fwd, x, logits = case.gpu_rank(rank, max_rows, packed=packed)
     for name, value in (knobs or {}).items():          # tuning knobs of the packed FFN
         setattr(fwd.args, name, value)
+    if cover:
+        rg, rd, ride_g, ride_d = fwd.tile_choice()
+        n = _assert_units_compared(case, rank, tokens, sorted({rg, rd}))
+        print(f"  rank {rank}: row-tiles of {rg} (gate/up) and {rd} (down) rows, riders {ride_g}/{ride_d}; "
+              f"{n} units of work all have compared rows", flush=True)
     out = fwd(x, logits)
     rows, ovf = fwd.result()
-    ref = case.oracle_rank(rank, tokens)
+    if ref is None:
+        ref = case.oracle_rank(rank, tokens)
     d = {k: _np(v) for k, v in fwd.debug.items()}
     assert np.array_equal(d["ids"], ref["ids"])
     assert np.allclose(d["topk_w"], ref["w"], rtol=1e-5, atol=1e-30)
@@ -485,35 +546,24 @@ def test_cold_slots_riding_with_busy_tiles(torch_cuda, T, H, I, E, k, D, slots, 
 
 # -------------------------------------------------- full-size configurations
 
-def _sampled_tokens(case: Case, rank: int, n: int):
-    """Tokens that have at least one row on the rank (plus a few that have none)."""
-    cfg = case.cfg
-    lo = int(case.slot_off[case.rank_slot_off[rank]])
-    hi = int(case.slot_off[case.rank_slot_off[rank + 1]])
-    d = case.dest.reshape(cfg.T, cfg.k)
-    on = np.nonzero(((d >= lo) & (d < hi)).any(1))[0]
-    off = np.nonzero(~((d >= lo) & (d < hi)).any(1))[0]
-    g = np.random.default_rng(1)
-    pick = list(g.choice(on, size=min(n, on.size), replace=False))
-    pick += list(off[:2])
-    # make sure the last row of the rank (ragged tail of the last tile) is covered
-    pick.append(int(case.src[hi - 1] // cfg.k))
-    return sorted(set(int(t) for t in pick))
-
-
 @pytest.mark.parametrize("name", ["qwen3", "dsv3", "kimi"])
-def test_full_size_heaviest_rank_sampled(torch_cuda, name):
-    # the launch configuration the benchmark times: full shapes, the heaviest rank's share;
-    # integer results checked everywhere, the output on sampled tokens the checker can afford
+def test_full_size_heaviest_rank_every_token(torch_cuda, name):
+    # the launch configuration the benchmark times: full shapes, the heaviest rank's share, the
+    # tile heights and rider switches the library picks by itself.  Integer results and the
+    # output of EVERY token are compared (the checker does a rank's rows in seconds), so every
+    # row of every row-tile, cold slot and rider unit of both GEMMs is looked at.
+    import time
     cfg = synth.CONFIGS[name]
     print("full size", cfg, flush=True)
     case = Case(cfg)
     g = case.heaviest
     print(f"  rows per rank: max={max(case.rows)} mean={np.mean(case.rows):.0f} heaviest={g} "
-          f"slots={case.rank_slots(g)}", flush=True)
-    toks = _sampled_tokens(case, g, 12)
-    _check_rank(torch_cuda, case, g, tokens=toks, packed=True)
-    _check_rank(torch_cuda, case, g, tokens=toks, packed=False)
+          f"slot rows={case.slot_cnt[case.rank_slot_off[g]:case.rank_slot_off[g + 1]].tolist()}", flush=True)
+    t0 = time.perf_counter()
+    ref = case.oracle_rank(g)
+    print(f"  checker: all {ref['rows']} rows, {cfg.T} tokens in {time.perf_counter() - t0:.1f} s", flush=True)
+    _check_rank(torch_cuda, case, g, packed=True, ref=ref, cover=True)
+    _check_rank(torch_cuda, case, g, packed=False, ref=ref)
 
 
 # ------------------------------------------------------------- 8-bit expert weights
@@ -547,4 +597,4 @@ def test_reduced_layers_with_e4m3_weights(torch_cuda, T, H, I, E, k, D, slots):
 def test_full_size_qwen3_with_e4m3_weights(torch_cuda):
     case = Case(synth.CONFIGS["qwen3"], w8=True)
     g = case.heaviest
-    _check_rank(torch_cuda, case, g, tokens=_sampled_tokens(case, g, 12), packed=True)
+    _check_rank(torch_cuda, case, g, packed=True, cover=True)          # every token

@@ -10,7 +10,7 @@ from oracle import plan_oracle as po
 from paper_2603_28768_amd import binding, synth
 
 from cases import Case
-from test_gpu_parity import _check_rank, _sampled_tokens, torch_cuda  # noqa: F401
+from test_gpu_parity import _check_rank
 
 pytestmark = pytest.mark.gpu
 
@@ -84,5 +84,60 @@ def test_stack_layer_forward_under_its_own_plan(torch_cuda, stack, which):
     case = Case(cfg, plan=plan, layer=layer, pop=pop)
     g = case.heaviest
     print(f"  rows: max={max(case.rows)} mean={np.mean(case.rows):.0f} slots={len(case.rank_slots(g))}", flush=True)
-    toks = _sampled_tokens(case, g, 8)
-    _check_rank(torch_cuda, case, g, tokens=toks, packed=True)
+    # every token of the 32768 (the checker needs some ten seconds for the rank's rows)
+    _check_rank(torch_cuda, case, g, packed=True, cover=True)
+
+
+# ------------------------------------- the paper's own planner and the comparison plans
+
+@pytest.fixture(scope="module")
+def other_plans(stack):
+    """From the GPU histogram of the trace: the paper's pipeline (Alg. 1 replay, Alg. 2) at
+    R = 8 and with the replication factor chosen automatically (Sec. 4.2.1 step 2), placement
+    only and uniform replication (the setups of Sec. 5.1), each equal to the checker's plan."""
+    from test_plan_host import _same, _same_paper
+    W = stack["W"]
+    Wl = W.tolist()
+    plans = {}
+    plans["paper_R8"] = binding.Plan(W, D, 8 * D, objective=1)
+    _same_paper(plans["paper_R8"], po.make_plan_paper(Wl, D, 8 * D))
+    plans["paper_auto"] = binding.Plan(W, D, 8 * D, objective=1, auto_r=True)
+    ref = po.make_plan_paper(Wl, D, 8 * D, True)
+    _same_paper(plans["paper_auto"], ref)
+    R = po.choose_replication_factor(ref["benefit"], D, 8)
+    assert plans["paper_auto"].benefit()["auto_R"] == R and ref["total_replicas"] <= R * D
+    plans["placement_only"] = binding.Plan(W, D, 0, objective=2)
+    _same(plans["placement_only"], po.make_plan_uniform(Wl, D, 0))
+    plans["uniform"] = binding.Plan(W, D, L * D, objective=2)
+    _same(plans["uniform"], po.make_plan_uniform(Wl, D, D))
+    return plans
+
+
+def test_paper_planner_and_comparison_plans_from_the_gpu_histogram(stack, other_plans):
+    def mean_bal(p):
+        return float(np.mean([p.layer(l)["est_balancedness"] for l in range(L)]))
+    bal = {k: mean_bal(p) for k, p in other_plans.items()}
+    bal["greedy_R8"] = mean_bal(stack["plan"])
+    print("  mean estimated balancedness:", {k: round(v, 4) for k, v in bal.items()}, flush=True)
+    assert other_plans["paper_R8"].summary()["total_replicas"] == 8 * D
+    assert other_plans["paper_R8"].summary()["memory_saving_vs_uniform"] == L / 8     # Sec. 5.2
+    assert other_plans["uniform"].summary()["memory_saving_vs_uniform"] == 1.0
+    # replication beats placement alone, and uniform replication with L / R times the memory
+    # is the upper end (Sec. 3.2)
+    assert bal["uniform"] > bal["paper_R8"] > bal["placement_only"]
+    assert bal["greedy_R8"] > bal["placement_only"]
+
+
+@pytest.mark.parametrize("which", ["paper_R8", "paper_auto", "placement_only", "uniform"])
+def test_layer_forward_under_the_paper_planner_and_comparison_plans(torch_cuda, stack, other_plans, which):
+    # a DeepSeek-V3-shaped layer (T = 8192) of the stack, the most skewed one, under each of
+    # those plans: heaviest rank's share, every token against the checker
+    plan, s = other_plans[which], stack["s"]
+    layer = int(np.argsort(s)[-1])
+    cfg = synth.scaled(synth.CONFIGS["dsv3_long"], T=8192, zipf_s=float(s[layer]))
+    pop = synth.popularity(E, s[layer], STACK_INDEX, layer)
+    case = Case(cfg, plan=plan, layer=layer, pop=pop)
+    g = case.heaviest
+    print(f"  {which}: layer {layer} replicas={plan.layer(layer)['n_replicas']} rows max={max(case.rows)} "
+          f"mean={np.mean(case.rows):.0f} slots={len(case.rank_slots(g))}", flush=True)
+    _check_rank(torch_cuda, case, g, packed=True, cover=True)

@@ -288,3 +288,4 @@ def test_gate_workspace_query_and_forward_workspace_with_own_gate():
     assert lib.craft_moe_rank_forward_workspace(plan._h, 0, 0, ctypes.byref(a), ctypes.byref(own)) == 0
     assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 4096, 4096, 128, ctypes.byref(n)) == 0
     assert own.value - given.value >= 4096 * 128 * 4 + n.value
+
