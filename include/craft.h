@@ -37,7 +37,8 @@ typedef enum {
     CRAFT_ENOMEM = -2,      /* host allocation failed */
     CRAFT_EHIP = -3,        /* a HIP runtime call or kernel launch failed */
     CRAFT_EWORKSPACE = -4,  /* workspace or table buffer too small */
-    CRAFT_EINFEASIBLE = -5  /* the request exceeds a fixed limit of the library */
+    CRAFT_EINFEASIBLE = -5  /* the request exceeds a fixed limit of the library (the static scratch of
+                               craft_moe_rank_forward_static) */
 } craft_status;
 
 const char *craft_status_str(craft_status s);
@@ -338,6 +339,28 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
                                               size_t *bytes);
 craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                     const craft_fwd_args *args, void *stream);
+
+/* The same forward for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc) and have no workspace to
+ * hand in: everything craft_moe_rank_forward keeps in `workspace` lives in a device array of
+ * CRAFT_STATIC_SCRATCH_BYTES that is part of the library (each GPU the library runs on holds
+ * its own copy until the process ends).  args->workspace and args->workspace_bytes are
+ * ignored; every other argument, the kernels and the results are those of
+ * craft_moe_rank_forward.  Neither this call nor anything it launches allocates or frees
+ * device memory; the first forward of a new (T, k, H, I) on a (layer, rank) notes its tile
+ * choice in the plan (a few bytes of host memory), and the first call on a device looks up
+ * the array's address there (make that call outside a capture).
+ *   CRAFT_EINFEASIBLE when craft_moe_rank_forward_workspace() for these arguments exceeds
+ *   CRAFT_STATIC_SCRATCH_BYTES (checked on the host before anything is launched: lower
+ *   max_rows or T); the other errors as craft_moe_rank_forward.
+ * All calls on one GPU share that GPU's array and the array keeps the last call's contents:
+ * forwards through this entry point must be ordered on one stream (calls that overlap on
+ * one GPU race), and craft_moe_rank_forward_result has no workspace pointer to read here
+ * (rows routed to the rank = slot_off[last slot of the rank + 1] - slot_off[its first slot]
+ * from the optional slot_off output; on overflow `out` is all zeros). */
+#define CRAFT_STATIC_SCRATCH_BYTES (64u << 20)
+craft_status craft_moe_rank_forward_static(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                           const craft_fwd_args *args, void *stream);
 
 /* How forwards with these arguments cut the two grouped GEMMs into tiles: the most rows a
  * row-tile gets (a multiple of 32), and whether the slots with few rows are carried along by

@@ -71,6 +71,7 @@ EXPORTS = {
                                                c_vp]),
     "craft_moe_rank_forward_workspace": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_sz)]),
     "craft_moe_rank_forward": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
+    "craft_moe_rank_forward_static": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), c_vp]),
     "craft_moe_rank_forward_tiles": (ctypes.c_int, [c_vp, c_i32, c_i32, P(FwdArgs), P(c_i32), P(c_i32),
                                                     P(c_i32), P(c_i32)]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
@@ -410,9 +411,10 @@ class RankForward:
         a.workspace_bytes = n.value
         self.args = a
 
-    def __call__(self, x, logits=None, stream=None):
+    def __call__(self, x, logits=None, stream=None, static_scratch=False):
         """Enqueue one forward; returns the (reused) output tensor.  `logits` is left out by a
-        forward that was given the gate's weights."""
+        forward that was given the gate's weights.  static_scratch: go through
+        craft_moe_rank_forward_static (the library's own scratch instead of the workspace)."""
         import torch
         assert x.dtype == _torch_dtype(self.dtype) and tuple(x.shape) == (self.T, self.H)
         assert x.is_contiguous()
@@ -424,9 +426,9 @@ class RankForward:
         else:
             assert logits is None
             self.args.logits = None
-        _check(lib().craft_moe_rank_forward(self.plan._h, self.layer, self.rank,
-                                            ctypes.byref(self.args), _stream_ptr(stream)),
-               "craft_moe_rank_forward")
+        entry = lib().craft_moe_rank_forward_static if static_scratch else lib().craft_moe_rank_forward
+        _check(entry(self.plan._h, self.layer, self.rank, ctypes.byref(self.args), _stream_ptr(stream)),
+               "craft_moe_rank_forward_static" if static_scratch else "craft_moe_rank_forward")
         return self.out
 
     def tile_choice(self):

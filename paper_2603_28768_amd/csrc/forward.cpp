@@ -429,7 +429,31 @@ craft_status craft_moe_rank_forward_workspace(const craft_plan_t *plan, int32_t 
 
 namespace {
 
-// One forward on `workspace`; `a` has passed check_fwd.
+// Scratch for craft_moe_rank_forward_static: device memory that lives in the library's code
+// object, one copy per GPU.  In host code this name only stands for the symbol; the address
+// on a given device comes from hipGetSymbolAddress (static_scratch below) and only that
+// pointer is ever handed to a kernel or a copy.
+constexpr size_t kStaticScratchBytes = (size_t)CRAFT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_on_device[kMaxDevices];
+
+// The array's address on the current device; resolved at the first call on each device.
+craft_status static_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CRAFT_EHIP;
+    void *p = g_scratch_on_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CRAFT_EHIP;
+        g_scratch_on_device[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return CRAFT_OK;
+}
+
+// One forward on `workspace` (the caller's, or the library's static scratch); `a` has passed
+// check_fwd.
 craft_status forward_on(const craft_plan_t *plan, int32_t layer, int32_t rank, const craft_fwd_args *a,
                         void *workspace, size_t workspace_bytes, void *stream) {
     if (!workspace || !aligned(workspace, 256) || !a->tables) return CRAFT_EINVAL;
@@ -553,6 +577,23 @@ craft_status craft_moe_rank_forward(const craft_plan_t *plan, int32_t layer, int
     craft_status st = check_fwd(plan, layer, rank, a);
     if (st != CRAFT_OK) return st;
     return forward_on(plan, layer, rank, a, a->workspace, a->workspace_bytes, stream);
+}
+
+craft_status craft_moe_rank_forward_static(const craft_plan_t *plan, int32_t layer, int32_t rank,
+                                           const craft_fwd_args *a, void *stream) {
+    craft_status st = check_fwd(plan, layer, rank, a);
+    if (st != CRAFT_OK) return st;
+    // sizes first (host arithmetic only): a request that does not fit is refused before any
+    // device is touched
+    const craft_layer_plan &lp = plan->layers[layer];
+    const int32_t nslots = lp.rank_slot_off[rank + 1] - lp.rank_slot_off[rank];
+    const Layout L = make_layout(a->T, a->k, plan->E, (int32_t)lp.slot_expert.size(), nslots, a->H, a->I,
+                                 a->dtype, a->max_rows, a->logits == nullptr);
+    if (L.total > kStaticScratchBytes) return CRAFT_EINFEASIBLE;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != CRAFT_OK) return st;
+    return forward_on(plan, layer, rank, a, ws, kStaticScratchBytes, stream);
 }
 
 craft_status craft_moe_rank_forward_tiles(const craft_plan_t *plan, int32_t layer, int32_t rank,

@@ -289,3 +289,20 @@ def test_gate_workspace_query_and_forward_workspace_with_own_gate():
     assert lib.craft_router_logits_workspace(binding.CRAFT_BF16, 4096, 4096, 128, ctypes.byref(n)) == 0
     assert own.value - given.value >= 4096 * 128 * 4 + n.value
 
+
+def test_static_scratch_forward_refuses_what_does_not_fit():
+    # host-side size check of craft_moe_rank_forward_static: no device is touched before it
+    lib = binding.lib()
+    g = np.random.default_rng(4)
+    W = g.multinomial(8 * 4096, synth.popularity(128, 1.0, 2, 0), size=(4, 1)).astype(np.int64)
+    plan = binding.Plan(W, 8, 8)
+    a = binding.FwdArgs()
+    a.dtype, a.T, a.H, a.I, a.k = 1, 4096, 4096, 1536, 8
+    a.logits = 0x1000
+    need = ctypes.c_size_t()
+    assert lib.craft_moe_rank_forward_workspace(plan._h, 0, 0, ctypes.byref(a), ctypes.byref(need)) == 0
+    assert need.value > (64 << 20)
+    assert lib.craft_moe_rank_forward_static(plan._h, 0, 0, ctypes.byref(a), None) == -5
+    assert b"limit" in lib.craft_status_str(-5)
+    a.k = 0                                                    # bad arguments are still bad arguments
+    assert lib.craft_moe_rank_forward_static(plan._h, 0, 0, ctypes.byref(a), None) == -1
