@@ -168,36 +168,41 @@ def greedy_allocation(Ws: Sequence[Sequence[int]], D: int,
 
 
 def mckp_allocation(Tmap: Dict[int, Sequence[float]], C: int) -> List[int]:
-    """Alg. 2: one replica count per layer from {0} + keys(T), total exactly C,
-    maximum total gain.  Keys are visited in ascending order and a candidate
-    replaces the incumbent only when strictly better.  Returns x, or raises when
-    no selection sums to C."""
-    keys = sorted(Tmap.keys())
-    L = len(Tmap[keys[0]])
-    NEG = None
-    dp = [[NEG] * (C + 1) for _ in range(L + 1)]
-    choice = [[None] * (C + 1) for _ in range(L + 1)]
-    dp[0][0] = 0
-    for l in range(1, L + 1):
-        j = l - 1
-        for c in range(C + 1):
-            dp[l][c] = dp[l - 1][c]
-            choice[l][c] = None
-            for r in keys:
-                if c >= r and dp[l - 1][c - r] is not NEG:
-                    cand = dp[l - 1][c - r] + Tmap[r][j]
-                    if dp[l][c] is NEG or cand > dp[l][c]:
-                        dp[l][c] = cand
-                        choice[l][c] = r
-    if dp[L][C] is NEG:
+    """Alg. 2: every layer takes one replica count, 0 or one of the counts Alg. 1 scored, the
+    counts add up to exactly C, and the summed gain is as large as possible.  Returns the count
+    per layer, or raises when no selection adds up to C.
+
+    One pass over the layers keeps, for every total c, the best summed gain the layers seen so
+    far can reach with exactly c replicas (None: unreachable), and remembers per layer which
+    count it took to get there.  A layer's options are tried as 0 first, then the scored counts
+    from the smallest up, and an option only displaces the one before it when strictly better:
+    equal gains keep fewer replicas.  The answer is read back from the last layer to the first.
+    """
+    counts = sorted(Tmap)
+    L = len(Tmap[counts[0]])
+    reach: List[Optional[float]] = [None] * (C + 1)      # reach[c]: best gain at total c so far
+    reach[0] = 0.0
+    took: List[List[int]] = []                           # took[l][c]: layer l's count in that best
+    for l in range(L):
+        after = list(reach)                              # this layer takes nothing
+        mine = [0] * (C + 1)
+        for r in counts:
+            gain = Tmap[r][l]
+            for c in range(r, C + 1):
+                if reach[c - r] is None:
+                    continue
+                v = reach[c - r] + gain
+                if after[c] is None or v > after[c]:
+                    after[c], mine[c] = v, r
+        took.append(mine)
+        reach = after
+    if reach[C] is None:
         raise ValueError("no selection of replica counts sums to C")
     x = [0] * L
-    c = C
-    for l in range(L, 0, -1):
-        r = choice[l][c]
-        if r is not None:
-            x[l - 1] = r
-            c -= r
+    left = C
+    for l in range(L - 1, -1, -1):
+        x[l] = took[l][left]
+        left -= x[l]
     return x
 
 
@@ -213,25 +218,27 @@ def interleave_select(idx: Sequence[int], k: int) -> List[int]:
 
 def capacity_assignment(D: int, R: Sequence[int]) -> List[List[int]]:
     """Alg. 3.  R[l] = physical experts (base + replicas) of layer l.
-    Returns A[l][g] = experts held by rank g in layer l."""
-    L = len(R)
-    A = [[R[l] // D] * D for l in range(L)]
-    G = [sum(A[l][g] for l in range(L)) for g in range(D)]
-    for l in range(L):
-        r = R[l] % D
-        if r == 0:
-            continue
-        cutoff = sorted(G)[r - 1]
-        M = [g for g in range(D) if G[g] < cutoff]
-        q = r - len(M)
-        if q > 0:
-            K = sorted(g for g in range(D) if G[g] == cutoff)
-            S = M + interleave_select(K, q)
-        else:
-            S = M
-        for g in S:
-            A[l][g] += 1
-            G[g] += 1
+    Returns A[l][g] = experts held by rank g in layer l.
+
+    Every rank holds floor(R[l] / D) experts of layer l; the R[l] mod D experts left over go
+    one each to the ranks that have collected the fewest such extras in the layers before
+    (the floors are the same for all ranks, so only the extras tell ranks apart).  Ranks are
+    taken in order of extras so far; the last level that only partly fits is a tie, and there
+    the takers are spread evenly over the tied ranks in rank order (interleave_select)."""
+    extras = [0] * D
+    A: List[List[int]] = []
+    for total in R:
+        row = [total // D] * D
+        need = total % D
+        if need:
+            by_fill = sorted(range(D), key=lambda g: (extras[g], g))
+            level = extras[by_fill[need - 1]]            # fill of the last rank that still gets one
+            below = [g for g in by_fill if extras[g] < level]
+            tied = [g for g in by_fill if extras[g] == level]
+            for g in below + interleave_select(tied, need - len(below)):
+                row[g] += 1
+                extras[g] += 1
+        A.append(row)
     return A
 
 
