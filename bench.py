@@ -291,7 +291,13 @@ def copy_calibration(args):
 # (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
 # is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-TRAFFIC = {}
+_SHA = "2cbafc96518e0623a04f0b76d0f786be7abdf8c7a722dd58a29d39c774a21716"
+TRAFFIC = {
+    "qwen3": dict(fetch_kib=293127.6, write_kib=15153.3, fetch_scale=2.0, write_scale=1.0, sources_sha256=_SHA),
+    "dsv3": dict(fetch_kib=198183.0, write_kib=11521.3, fetch_scale=2.0, write_scale=1.0, sources_sha256=_SHA),
+    "kimi": dict(fetch_kib=177146.7, write_kib=11947.6, fetch_scale=2.0, write_scale=1.0, sources_sha256=_SHA),
+    "stack": dict(fetch_kib=2306827.2, write_kib=83593.3, fetch_scale=2.0, write_scale=1.0, sources_sha256=_SHA),
+}
 
 
 def kernel_sources_sha256():
@@ -318,12 +324,20 @@ def machine_rates(steps=10):
     n = 256 << 20
     a = torch.ones(n, dtype=torch.uint8, device="cuda")
     b = torch.empty_like(a)
-    sink = torch.empty(2 * 1024 * 256, dtype=torch.float32, device="cuda")
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    sink = torch.empty(8 * 1024 * 256, dtype=torch.float32, device="cuda")
+    isink = torch.empty(8 * 1024 * 256, dtype=torch.int32, device="cuda")
+    small = torch.ones(2 << 20, dtype=torch.uint8, device="cuda")     # fits every XCD's L2
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
     for _ in range(3):
         binding.probe_copy(a, b)
         binding.probe_mfma_bf16(2000, sink)
+        binding.probe_read(small, 2, isink)
     torch.cuda.synchronize()
+    ev[4].record()
+    l2_bytes = 0.0
+    for _ in range(steps):
+        l2_bytes += binding.probe_read(small, 8, isink)
+    ev[5].record()
     ev[0].record()
     for _ in range(steps):
         binding.probe_copy(a, b)
@@ -336,7 +350,8 @@ def machine_rates(steps=10):
     torch.cuda.synchronize()
     assert bool((b == 1).all())
     return dict(copy_gbs=2.0 * n * steps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
-                mfma_bf16_tflops=flops / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e12)
+                mfma_bf16_tflops=flops / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e12,
+                l2_read_gbs=l2_bytes / (ev[4].elapsed_time(ev[5]) * 1e-3) / 1e9)
 
 
 def cpu_model():
@@ -552,10 +567,12 @@ def main():
                                 frac_of_no_overlap=no_ov / ffn_ms if ffn_ms else None,
                                 frac_of_perfect_overlap=perfect / ffn_ms if ffn_ms else None),
                 machine=dict(copy_gbs=rates["copy_gbs"], mfma_bf16_tflops=rates["mfma_bf16_tflops"],
+                             l2_read_gbs=rates["l2_read_gbs"],
                              frac_of_measured_copy=gbs / rates["copy_gbs"],
                              frac_of_measured_mfma=tfs / rates["mfma_bf16_tflops"],
-                             what="craft_probe_copy of 256 MiB (bytes read + written per second) and "
-                                  "craft_probe_mfma_bf16 (register-only v_mfma_f32_32x32x16_bf16 loop) on this GPU"))
+                             what="craft_probe_copy of 256 MiB (bytes read + written per second), "
+                                  "craft_probe_mfma_bf16 (register-only v_mfma_f32_32x32x16_bf16 loop) and "
+                                  "craft_probe_read (every workgroup re-reading a 2 MiB buffer out of L2) on this GPU"))
 
     if len(states) == 1:
         workload = (f"{cfg.name}: T={cfg.T} H={cfg.H} E={cfg.E} top-{cfg.k} I={cfg.I} Zipf s={cfg.zipf_s}, "

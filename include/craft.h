@@ -410,8 +410,16 @@ craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_
  *   v_mfma_f32_32x32x16_bf16 on register operands (no memory traffic but the final store of one
  *   float per thread to sink, DEVICE [blocks * 256]); *flops = the floating-point operations
  *   the launch performs (2 * 32 * 32 * 16 per MFMA).  blocks = 0: two per compute unit.
- * Both only enqueue on `stream`; time them with events on that stream. */
+ * craft_probe_read: each of `blocks` workgroups (0: eight per compute unit) reads all of src
+ *   (`bytes`, a multiple of 32 KiB, DEVICE, 16-byte aligned) `passes` times and stores one
+ *   word per thread to sink (DEVICE [blocks * 256] uint32); *bytes_read = what the launch
+ *   requests in total.  With a buffer of a megabyte or two, which the L2 of every XCD holds
+ *   and the L1 of a compute unit does not, this measures what all compute units together
+ *   can pull out of L2.
+ * All only enqueue on `stream`; time them with events on that stream. */
 craft_status craft_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+craft_status craft_probe_read(const void *src, int64_t bytes, int32_t passes, int32_t blocks,
+                              uint32_t *sink, double *bytes_read, void *stream);
 craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, double *flops,
                                    void *stream);
 

@@ -76,6 +76,7 @@ EXPORTS = {
                                                     P(c_i32), P(c_i32)]),
     "craft_moe_rank_forward_result": (ctypes.c_int, [c_vp, P(c_i64), P(c_i32)]),
     "craft_probe_copy": (ctypes.c_int, [c_vp, c_vp, c_i64, c_vp]),
+    "craft_probe_read": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
     "craft_probe_mfma_bf16": (ctypes.c_int, [c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
     "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
     "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
@@ -458,6 +459,15 @@ def probe_copy(src, dst, stream=None):
     """dst <- src (device uint8 tensors of equal size, a multiple of 16 bytes)."""
     assert src.numel() == dst.numel() and src.element_size() == dst.element_size() == 1
     _check(lib().craft_probe_copy(_dev(src), _dev(dst), src.numel(), _stream_ptr(stream)), "craft_probe_copy")
+
+
+def probe_read(src, passes: int, sink, blocks: int = 0, stream=None) -> float:
+    """Enqueue the read loop over src (device uint8, a multiple of 32 KiB); returns the bytes it
+    requests.  sink: device int32 tensor with at least blocks * 256 elements (0: 8 per CU)."""
+    n = ctypes.c_double()
+    _check(lib().craft_probe_read(_dev(src), src.numel(), passes, blocks, _dev(sink), n, _stream_ptr(stream)),
+           "craft_probe_read")
+    return n.value
 
 
 def probe_mfma_bf16(iters: int, sink, blocks: int = 0, stream=None) -> float:

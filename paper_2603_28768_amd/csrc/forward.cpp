@@ -628,6 +628,16 @@ craft_status craft_probe_copy(const void *src, void *dst, int64_t bytes, void *s
                                                                                                  : CRAFT_EHIP;
 }
 
+craft_status craft_probe_read(const void *src, int64_t bytes, int32_t passes, int32_t blocks, uint32_t *sink,
+                              double *bytes_read, void *stream) {
+    if (bytes <= 0 || bytes % (32 << 10) || passes <= 0 || blocks < 0 || blocks > (1 << 20)) return CRAFT_EINVAL;
+    if (!src || !sink || !aligned(src, 16) || !aligned(sink, 4)) return CRAFT_EINVAL;
+    if (blocks == 0) blocks = 8 * cached_num_cu();
+    if (bytes_read) *bytes_read = (double)blocks * (double)passes * (double)bytes;
+    return launch_probe_read(src, bytes, passes, blocks, sink, as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                                 : CRAFT_EHIP;
+}
+
 craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, double *flops, void *stream) {
     if (blocks < 0 || blocks > (1 << 20) || iters <= 0 || !sink || !aligned(sink, 4)) return CRAFT_EINVAL;
     if (blocks == 0) blocks = 2 * cached_num_cu();
