@@ -390,8 +390,8 @@ craft_status craft_moe_rank_forward_result(const void *workspace, int64_t *rows,
  */
 enum {
     CRAFT_K_ROUTE = 0,     /* top-k + per-block ranks */
-    CRAFT_K_SCAN = 1,      /* per-expert scan, slot offsets, tile table */
-    CRAFT_K_DISPATCH = 2,  /* dest / src */
+    CRAFT_K_SCAN = 1,      /* per-expert scan, slot offsets */
+    CRAFT_K_DISPATCH = 2,  /* dest / src, tile tables of the GEMMs */
     CRAFT_K_GATEUP = 3,    /* grouped gate/up GEMM + SwiGLU (gathers its rows) */
     CRAFT_K_DOWN = 4,      /* grouped down GEMM */
     CRAFT_K_COMBINE = 5,   /* weighted combine */

@@ -17,8 +17,9 @@ constexpr int kScanWaves = kScanThreads / 64;
 static_assert(kScanChunk % kScanWaves == 0, "a chunk is dealt to the waves in equal parts");
 
 // Exclusive scan over the workgroup of one value per thread (wave shuffles, then one LDS
-// exchange between the 16 waves).  Returns the exclusive prefix; *total gets the sum.
-__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum /*[kScanWaves]*/,
+// exchange between the WAVES waves).  Returns the exclusive prefix; *total gets the sum.
+template <int WAVES>
+__device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum /*[WAVES]*/,
                                                         int32_t *total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t inc = v;
@@ -32,7 +33,7 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum
     __syncthreads();
     int32_t before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < kScanWaves; ++w) {
+    for (int w = 0; w < WAVES; ++w) {
         const int32_t s = wsum[w];
         if (w < wave) before += s;
         all += s;
@@ -48,8 +49,8 @@ __device__ __forceinline__ int32_t block_exclusive_scan(int32_t v, int32_t *wsum
 // per-block counts are rewritten as exclusive prefixes inside the chunk.  With several
 // chunks the chunk totals go to memory and the workgroup that finishes last (ticket
 // counter) turns them into per-chunk bases, which the dispatch kernel adds.  That workgroup
-// (trivially the only one) also derives everything that needs all counts: rows per slot,
-// slot offsets, the rank's row count and the row-tile tables of the grouped GEMMs.
+// (trivially the only one) also derives what needs all counts and what the dispatch indices
+// wait for: rows per slot, slot offsets and the rank's row count.
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     __shared__ int32_t part[kScanWaves][64];
     __shared__ int32_t wsum[kScanWaves];
@@ -135,9 +136,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
 
     // rows of slot p: tokens i < n of its expert with i mod c == q.  Slots are taken in
     // chunks of one per thread; `carry` is the running offset across chunks.
-    // The rank's own slot rows and the two offsets that bound its rows stay in LDS: reading
-    // them back from global memory would be two more dependent round trips in this serial tail.
-    __shared__ int32_t rank_slot_rows[1024];
+    // The two offsets that bound the rank's rows stay in LDS: reading them back from global
+    // memory would be one more dependent round trip in this serial tail.
     __shared__ int32_t bound_pos[2];
     int32_t carry = 0, lo_pos = 0, hi_pos = 0;
     for (int32_t base = 0; base < a.S; base += kScanThreads) {
@@ -149,13 +149,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
             r = n > q ? (n - q + c - 1) / c : 0;
         }
         int32_t chunk_total;
-        const int32_t off = carry + block_exclusive_scan(r, wsum, &chunk_total);
+        const int32_t off = carry + block_exclusive_scan<kScanWaves>(r, wsum, &chunk_total);
         if (p < a.S) {
             a.slot_cnt[p] = r;
             a.slot_off[p] = off;
             if (a.user_slot_cnt) a.user_slot_cnt[p] = r;
             if (a.user_slot_off) a.user_slot_off[p] = off;
-            if (p >= a.s_lo && p < a.s_hi) rank_slot_rows[p - a.s_lo] = r;
             if (p == a.s_lo) bound_pos[0] = off;
             if (p == a.s_hi) bound_pos[1] = off;
         }
@@ -171,11 +170,32 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     // this rank's rows; refuse the batch when they exceed the staging buffers
     const int32_t rank_rows = hi_pos - lo_pos;
     const bool ovf = (int64_t)rank_rows > a.max_rows;
+    if (threadIdx.x == 0) {
+        a.ctrl[CTRL_ROWS] = rank_rows;
+        a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
+        a.ctrl[CTRL_TICKET] = 0;
+    }
+}
+
+// What the grouped GEMMs need beyond the slot offsets: the rank's slots ordered by rows, the
+// row-tile prefixes of both GEMMs over that order and the rider units.  None of it is needed
+// for the dispatch indices, so it is built by one extra workgroup of the dispatch launch
+// while the others write dest / src, instead of at the end of the scan's serial tail.
+constexpr int kTableThreads = 256;
+__device__ void build_tile_tables(const DispatchArgs &a) {
+    __shared__ int32_t rank_slot_rows[1024];
+    __shared__ int32_t sorted_rows[1024];
+    __shared__ int32_t wsum[kTableThreads / 64];
+    __shared__ int32_t prefix_len[3];
+    __shared__ int32_t hot_mtiles;
     const int32_t nslots = a.s_hi - a.s_lo;
+    const bool ovf = a.ctrl[CTRL_OVERFLOW] != 0;
+    for (int32_t sl = threadIdx.x; sl < nslots; sl += kTableThreads) rank_slot_rows[sl] = a.slot_cnt[a.s_lo + sl];
+    if (threadIdx.x < 3) prefix_len[threadIdx.x] = 0;
+    __syncthreads();
     // Order the rank's slots by rows, busiest first (ties: lower slot), so the tile list
     // starts with the matrix-bound tiles and ends with the cheap weight-streaming ones.
-    __shared__ int32_t sorted_rows[1024];
-    for (int32_t sl = threadIdx.x; sl < nslots; sl += kScanThreads) {
+    for (int32_t sl = threadIdx.x; sl < nslots; sl += kTableThreads) {
         const int32_t mine = rank_slot_rows[sl];
         int32_t pos = 0;
         for (int32_t j = 0; j < nslots; ++j) {
@@ -188,10 +208,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     __syncthreads();
     // the busy and the live slots are prefixes of the busiest-first order, and so are the slots
     // with more than one fragment
-    __shared__ int32_t prefix_len[3];
-    if (threadIdx.x < 3) prefix_len[threadIdx.x] = 0;
-    __syncthreads();
-    for (int32_t pos = threadIdx.x; pos < nslots; pos += kScanThreads) {
+    for (int32_t pos = threadIdx.x; pos < nslots; pos += kTableThreads) {
         const int32_t r = sorted_rows[pos], nxt = pos + 1 < nslots ? sorted_rows[pos + 1] : 0;
         if (r > kColdRows && nxt <= kColdRows) prefix_len[0] = pos + 1;
         if (r > 0 && nxt <= 0) prefix_len[1] = pos + 1;
@@ -203,27 +220,33 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
     const int32_t ncold2 = max(0, min(prefix_len[2], live) - hot);   // cold slots with two fragments
     // row-tiles per slot: its 32-row fragments over the launch's tile height, rounded up
     int32_t mtotal[2], riders[2];
-    __shared__ int32_t hot_mtiles;
     for (int kind = 0; kind < 2; ++kind) {
         const int32_t fmax = abs(kind == 0 ? a.frags_gu : a.frags_dn);
         int32_t *mt_out = a.mt_start + kind * (nslots + 1);
-        const int32_t pos = threadIdx.x;           // at most kScanThreads slots per rank
-        const int32_t F = pos < nslots && !ovf ? (sorted_rows[pos] + 31) >> 5 : 0;
-        const int32_t mt = (F + fmax - 1) / fmax;
-        int32_t mcarry;
-        const int32_t off = block_exclusive_scan(mt, wsum, &mcarry);
-        if (pos < nslots) mt_out[pos] = off;
-        if (pos == hot) hot_mtiles = off;          // row-tiles of the busy slots
-        if (threadIdx.x == 0 && hot >= kScanThreads) hot_mtiles = mcarry;
-        if (threadIdx.x == 0) mt_out[nslots] = mcarry;
-        mtotal[kind] = mcarry;
+        int32_t carry = 0;
+        if (threadIdx.x == 0) hot_mtiles = 0;
+        __syncthreads();
+        for (int32_t base = 0; base < nslots; base += kTableThreads) {
+            const int32_t pos = base + threadIdx.x;
+            const int32_t F = pos < nslots && !ovf ? (sorted_rows[pos] + 31) >> 5 : 0;
+            const int32_t mt = (F + fmax - 1) / fmax;
+            int32_t chunk_total;
+            const int32_t off = carry + block_exclusive_scan<kTableThreads / 64>(mt, wsum, &chunk_total);
+            if (pos < nslots) mt_out[pos] = off;
+            if (pos == hot) hot_mtiles = off;      // row-tiles of the busy slots
+            carry += chunk_total;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) mt_out[nslots] = carry;
+        if (threadIdx.x == 0 && hot >= nslots) hot_mtiles = carry;
+        mtotal[kind] = carry;
         __syncthreads();
         // rider units: one per tile of the busy slots while they last; a two-fragment slot
         // (4 nt units) is carried whole or not at all
         const int64_t nt = kind == 0 ? a.nt_gu : a.nt_dn;
         const int64_t units2 = (int64_t)ncold2 * 4 * nt, units = units2 + (int64_t)(ncold - ncold2) * 2 * nt;
         int64_t carried = fmax <= kRiderHostFrags ? min((int64_t)hot_mtiles * nt, units) : 0;
-        if (carried < units2) carried = carried / (4 * nt) * (4 * nt);
+        if (nt > 0 && carried < units2) carried = carried / (4 * nt) * (4 * nt);
         riders[kind] = (int32_t)carried;
         __syncthreads();                           // hot_mtiles is rewritten by the next kind
     }
@@ -233,14 +256,15 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(ScanArgs a) {
         a.ctrl[CTRL_COLD2_SLOTS] = ncold2;
         a.ctrl[CTRL_RIDERS_GATEUP] = riders[0];
         a.ctrl[CTRL_RIDERS_DOWN] = riders[1];
-        a.ctrl[CTRL_ROWS] = rank_rows;
-        a.ctrl[CTRL_OVERFLOW] = ovf ? 1 : 0;
         a.ctrl[CTRL_MTILES] = mtotal[0];
-        a.ctrl[CTRL_TICKET] = 0;
     }
 }
 
 __global__ __launch_bounds__(256) void dispatch_kernel(DispatchArgs a) {
+    if (blockIdx.x == gridDim.x - 1) {             // the extra workgroup: tile tables of the GEMMs
+        build_tile_tables(a);
+        return;
+    }
     const craft_tables_header *hdr = reinterpret_cast<const craft_tables_header *>(a.tables);
     const int32_t *copies = a.tables + hdr->off_copies;
     const int32_t *efirst = a.tables + hdr->off_efirst;
@@ -279,7 +303,7 @@ hipError_t launch_scan(const ScanArgs &a, hipStream_t s) {
 hipError_t launch_dispatch(const DispatchArgs &a, hipStream_t s) {
     if (a.T == 0) return hipSuccess;
     const int64_t nb = (a.T + kTokPerBlock - 1) / kTokPerBlock;
-    hipLaunchKernelGGL(dispatch_kernel, dim3((unsigned)nb), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(dispatch_kernel, dim3((unsigned)nb + 1), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -530,16 +530,17 @@ craft_status forward_on(const craft_plan_t *plan, int32_t layer, int32_t rank, c
     // 2 per-expert totals, slot offsets, tile table
     {
         ScopedEvent ev(CRAFT_K_SCAN, s);
-        ScanArgs sa{hist, chunk_tot, chunk_base, (int32_t)L.NB, E, tables, S, s_lo, s_hi, tiles.frags[0], tiles.frags[1], L.max_rows,
-                    counts, slot_cnt, slot_off, mt_start, order, tiles.riders[0] ? (a->I + 127) / 128 : 0,
-                    tiles.riders[1] ? (a->H + 255) / 256 : 0, ctrl,
-                    a->counts, a->slot_cnt, a->slot_off};
+        ScanArgs sa{hist, chunk_tot, chunk_base, (int32_t)L.NB, E, tables, S, s_lo, s_hi, L.max_rows,
+                    counts, slot_cnt, slot_off, ctrl, a->counts, a->slot_cnt, a->slot_off};
         if (launch_scan(sa, s) != hipSuccess) return CRAFT_EHIP;
     }
-    // 3 dispatch permutation
+    // 3 dispatch permutation (and, beside it, the tile tables of the two GEMMs)
     {
         ScopedEvent ev(CRAFT_K_DISPATCH, s);
-        DispatchArgs da{ids_out, lrank, hist, chunked ? chunk_base : nullptr, a->T, a->k, E, tables, slot_off, dest, src, a->dest, a->src};
+        DispatchArgs da{ids_out, lrank, hist, chunked ? chunk_base : nullptr, a->T, a->k, E, tables, slot_off, dest, src,
+                        a->dest, a->src, slot_cnt, s_lo, s_hi, tiles.frags[0], tiles.frags[1],
+                        tiles.riders[0] ? (a->I + 127) / 128 : 0, tiles.riders[1] ? (a->H + 255) / 256 : 0,
+                        mt_start, order, ctrl};
         if (launch_dispatch(da, s) != hipSuccess) return CRAFT_EHIP;
     }
     // 4 grouped FFN

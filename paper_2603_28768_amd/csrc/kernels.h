@@ -83,15 +83,10 @@ struct ScanArgs {
     int32_t NB, E;
     const int32_t *tables;    // device tables of this (layer, rank)
     int32_t S, s_lo, s_hi;
-    int32_t frags_gu, frags_dn;   // most 32-row fragments per row-tile, gate/up and down GEMM (sign: see FfnArgs)
     int64_t max_rows;
     int32_t *counts;          // [E]
     int32_t *slot_cnt;        // [S]
     int32_t *slot_off;        // [S+1]
-    int32_t *mt_start;        // [2][s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot
-                              // first: for the gate/up GEMM, then for the down GEMM
-    int32_t *order;           // [s_hi - s_lo] local slot at each position of that order
-    int32_t nt_gu, nt_dn;     // column tiles per slot of the two packed GEMMs; 0: no riders
     int32_t *ctrl;
     int32_t *user_counts, *user_slot_cnt, *user_slot_off;   // optional copies
 };
@@ -108,6 +103,15 @@ struct DispatchArgs {
     const int32_t *slot_off;
     int32_t *dest, *src;
     int32_t *user_dest, *user_src;
+    // for the extra workgroup that builds the tile tables of the grouped GEMMs
+    const int32_t *slot_cnt;  // [S] rows per slot
+    int32_t s_lo, s_hi;       // the rank's slots
+    int32_t frags_gu, frags_dn;   // most 32-row fragments per row-tile, gate/up and down GEMM (sign: see FfnArgs)
+    int32_t nt_gu, nt_dn;     // column tiles per slot of the two packed GEMMs; 0: no riders
+    int32_t *mt_start;        // [2][s_hi - s_lo + 1] row-tile prefix over the rank's slots, busiest slot
+                              // first: for the gate/up GEMM, then for the down GEMM
+    int32_t *order;           // [s_hi - s_lo] local slot at each position of that order
+    int32_t *ctrl;
 };
 hipError_t launch_dispatch(const DispatchArgs &a, hipStream_t s);
 
