@@ -316,6 +316,19 @@ def measured_traffic(cfg_name, packed):
     return (t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024.0
 
 
+def measured_counters(cfg_name, packed):
+    """The gate/up kernel's matrix-core and L2 counters from profiles/rank_forward_<workload>_
+    mfma_l2_counters.txt, under the same condition as the traffic figure."""
+    t = TRAFFIC.get(cfg_name)
+    if t is None or not packed or t["sources_sha256"] != kernel_sources_sha256() or "mfma_util" not in t:
+        return None
+    return dict(mfma_util=t["mfma_util"], mfma_busy_of_peak_clock=t["mfma_busy_of_peak_clock"],
+                l2_to_cu_bytes=t["l2_to_cu_mb"] * 1e6, l2_hit=t["l2_hit"],
+                what="rocprofv3 counters of the gate/up kernel per launch: MfmaUtil = SQ_VALU_MFMA_BUSY_CYCLES / "
+                     "(GRBM_GUI_ACTIVE per XCD x 1024 SIMDs); the same busy cycles over the cycles of the launch "
+                     "at 2.4 GHz; TCP_TCC_READ_REQ x 128 B; TCC_HIT / TCC_REQ")
+
+
 def machine_rates(steps=10):
     """This machine's own ceilings, measured with the library's probes on the current stream: a
     plain 256 MiB copy (bytes read + written per second) and a register-only bf16 MFMA loop."""
@@ -536,6 +549,7 @@ def main():
     else:
         roof = dict(bound="mfma" if cfg.dtype == "bf16" else "alu", achieved=tfs, peak=flop_peak,
                     unit="TFLOP/s", frac=tfs / flop_peak, traffic=traffic)
+    roof.update(counters=measured_counters(args.config, packed and not e4m3))
     roof.update(kernel="grouped gate/up GEMM + SwiGLU", avg_ms=gu_ms,
                 launches=times["gateup"]["launches"], algorithmic_bytes=gu_bytes,
                 algorithmic_flops=gu_flops, hbm_frac=gbs / HBM_PEAK_GBS, flop_frac=tfs / flop_peak,
@@ -601,6 +615,7 @@ def main():
     if not args.no_cpu_baseline:
         base = cpu_baseline(states[0]["cfg"], states[0])
         base["cpu_model"] = cpu_model()
+        base["build"] = "gcc -O2 -fopenmp, one thread per row of a slot"
         if n_l > 1:
             base["sample"] = f"layer {states[0]['layer']} of the {n_l} executed layers: " + base["sample"]
         out["cpu_baseline"] = base

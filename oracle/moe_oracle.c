@@ -10,13 +10,13 @@
  * representable in their storage type).
  *
  * What is computed, and where the paper defines it:
- *   oracle_router_logits Sec. 2.1: "a lightweight gating network computes a score for
- *                        each expert": read as the usual linear gate, score[t][e] =
- *                        x[t] . W_r[e], no bias (the paper gives no form).
- *   oracle_route         Sec. 2.1: a gating network scores every expert, the
- *                        top-K scores are activated, outputs are weighted.
- *   oracle_expert_load   Sec. 3.1 "expert load" = tokens dispatched to an expert
- *                        after routing; Alg. 1 input W[b][l][e].
+ *   oracle_router_logits Sec. 2.1 (routing): per-token expert scores from a gating network
+ *                        whose form the paper leaves open; read as the usual linear
+ *                        gate, score[t][e] = x[t] . W_r[e], no bias.
+ *   oracle_route         Sec. 2.1 (routing): top-K of the scores per token, with the
+ *                        routing weights of the K picked.
+ *   oracle_expert_load   Sec. 3.1 "expert load", the W[b][l][e] input of Alg. 1: routed
+ *                        assignments per expert, per batch and layer.
  *   oracle_dispatch      Sec. 1 / Alg. 1: a replicated expert's tokens are spread
  *                        evenly over its copies; the i-th token of expert e goes
  *                        to copy i mod c_e.

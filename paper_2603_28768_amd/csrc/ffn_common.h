@@ -28,14 +28,14 @@ struct Tile {
 //
 // Inside a slot the m x nt tiles are listed column by column, or (`blocked`) block by block:
 // bands of kBandRows row-tiles, a band cut into blocks of kBlockCols column tiles, a block
-// column by column.  A run of
-// kBandRows * kBlockCols consecutive list entries is then a compact rectangle of tiles that
-// needs kBandRows row-tiles of activations and kBlockCols column tiles of weights between
-// them.  Runs of the list are what one XCD works on at a time (see the tile queues of the
-// packed kernels), so its L2 serves each operand to several tiles instead of fetching the
-// activations once per column tile: at T = 32768 the gate/up GEMM pulled 4.7 GB per launch
-// through the fabric for 0.6 GB of operands when a run was one column of many row-tiles.
-constexpr int kBandRows = 4;
+// column by column.  A run of consecutive list entries, which is what runs at one time (tiles
+// are handed out in list order), is then a compact rectangle of tiles that needs few row-tiles
+// of activations and few column tiles of weights between them, where a run of the column
+// order needs every row-tile of the slot for each of its columns.  At T = 32768 (five rounds of
+// tiles) the step is 4 % faster with 8 x 8 blocks than column by column (4 x 8, 8 x 4: 3 %;
+// 2 x 16, 16 x 16, 1 x 8: 2 %); the packed kernels use the block order for launches of more
+// than two rounds.
+constexpr int kBandRows = 8;
 constexpr int kBlockCols = 8;
 struct TileTables {
     static constexpr int kMaxSlots = 256;

@@ -37,14 +37,13 @@
 //   * Row fragments beyond a tile's valid rows are skipped entirely (loads, LDS traffic,
 //     MFMAs): a slot with 20 rows costs one eighth of the matrix work of a full tile while
 //     streaming the same weights.
-//   * Tiles are listed busiest slot first, inside a slot as compact blocks of row-tiles x
-//     column tiles (ffn_common.h).  The list is dealt to the eight XCDs in runs as long as an
-//     XCD has workgroups: each XCD has a queue of its own (an atomic counter per XCD), its
-//     workgroups take their first tile by position and then the next entries of that queue,
-//     so the tiles an XCD runs at any time share activation rows and weight columns in its
-//     L2.  A workgroup whose queue has run dry moves on to the next XCD's queue, so the end
-//     of the launch is balanced tile by tile.  The cheap streaming tiles of the cold slots
-//     come last in the list, or ride along with busy tiles (see kRiderHostFrags in kernels.h).
+//   * Tiles are listed busiest slot first; in a launch of several rounds a slot's tiles come
+//     as compact blocks of row-tiles x column tiles (ffn_common.h), so that the tiles running
+//     at any time share activation rows and weight columns in the caches.  Each workgroup
+//     takes one tile by position (the XCD-aware mapping of ffn_common.h, so neighbours in the
+//     list start together on one XCD), then pulls further tiles from an atomic counter: the
+//     cheap streaming tiles of the cold slots fill in behind the matrix-bound ones, or ride
+//     along with them (see kRiderHostFrags in kernels.h).
 #include "ffn_common.h"
 
 namespace craft {
@@ -397,7 +396,6 @@ template <bool GATEUP, bool W8>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
     __shared__ int64_t next_item;
-    __shared__ int32_t next_queue;
     __shared__ TileTables tt;
     const int wave_id = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
     const int32_t *mt_start = a.mt_start + (GATEUP ? 0 : a.nslots + 1);
@@ -425,20 +423,10 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     const int64_t total = hot_tiles + cold_tiles;
     const int32_t lo_pos = a.slot_off[a.s_lo];
     const int32_t fmax = GATEUP ? a.frags_gu : a.frags_dn;
-    // The tile queues.  Workgroup b runs on XCD b mod 8 (workgroups are dealt to the XCDs in
-    // turn) and is one of `per` workgroups there.  Queue x is every eighth run of `per` list
-    // entries, starting with run x: its entry s is list entry ((s / per) * 8 + x) * per + s mod per.
-    // A workgroup's first entry is its own position in the XCD; the queue's counter hands out
-    // the entries from `per` on.
-    // Queues of their own (and the slots' tiles listed block by block) pay once the busy tiles
-    // make up several rounds over the CUs; with a round or two the end of the launch is what
-    // counts, and one queue for all (counter 0, the list in order, column by column) packs
-    // that best.
-    int32_t *const counters = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
-    const int64_t per = gridDim.x >> 3;
-    const bool own_queues = hot_tiles > 2 * (int64_t)gridDim.x;
-    auto entry = [&](int32_t x, int64_t s) { return own_queues ? ((s / per) * 8 + x) * per + s % per : s; };
-    int32_t queue = own_queues ? (int32_t)(blockIdx.x & 7) : 0;
+    // A launch of more than two rounds of busy tiles lists a slot's tiles block by block
+    // (ffn_common.h); a shorter one column by column, which packs its end best.
+    int32_t *const counter = a.ctrl + (GATEUP ? CTRL_WORK_GATEUP : CTRL_WORK_DOWN);
+    const bool blocked = hot_tiles > 2 * (int64_t)gridDim.x;
     // whole slot at position pos of the busiest-first order, as a tile
     auto slot_tile = [&](int32_t pos) {
         Tile t;
@@ -452,13 +440,12 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
         return t;
     };
 
-    int64_t w = (int64_t)(blockIdx.x & 7) * per + (blockIdx.x >> 3);     // first tile by position, the rest on demand
+    int64_t w = xcd_major_id();                    // first tile by position, the rest on demand
     while (w < total) {
         int32_t claimed = 0;                       // thread 0: the counter's answer, fetched inside the tile
-        int32_t *const counter = counters + queue;
         if (w < hot_tiles) {
-            const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax, own_queues)
-                                 : decode_tile(a, mt_start, w, nt, BN, fmax, own_queues);
+            const Tile t = small ? decode_tile(a, tt, w, nt, BN, fmax, blocked)
+                                 : decode_tile(a, mt_start, w, nt, BN, fmax, blocked);
             const int frags = (t.rows + 31) >> 5;  // live 32-row fragments of this tile
             Tile r = t;
             bool ride = w < carried && frags <= kRiderHostFrags;
@@ -508,21 +495,9 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
                 claimed = (int32_t)atomicInc(reinterpret_cast<unsigned int *>(counter), 0xffffffffu);
             }
         }
-        if (wave_id == 0 && lane_index() == 0) {
-            // the next entry of the queue this workgroup draws from; a queue that has run dry
-            // sends it on to the next XCD's (each of the other seven is tried once at most)
-            int32_t x = queue;
-            int64_t nw = entry(x, (own_queues ? per : (int64_t)gridDim.x) + claimed);
-            for (int tries = 0; own_queues && nw >= total && tries < 7; ++tries) {
-                x = (x + 1) & 7;
-                nw = entry(x, per + (int64_t)atomicInc(reinterpret_cast<unsigned int *>(counters + x), 0xffffffffu));
-            }
-            next_item = nw;
-            next_queue = x;
-        }
+        if (wave_id == 0 && lane_index() == 0) next_item = (int64_t)gridDim.x + claimed;
         __syncthreads();
         w = next_item;
-        queue = __builtin_amdgcn_readfirstlane(next_queue);
         __syncthreads();
     }
 }

@@ -22,8 +22,8 @@ enum { CTRL_TICKET = 0, CTRL_ROWS = 1, CTRL_OVERFLOW = 2, CTRL_MTILES = 3,
        CTRL_LIVE_SLOTS = 7,                        // slots of the rank with any rows
        CTRL_RIDERS_GATEUP = 8, CTRL_RIDERS_DOWN = 9,   // rider units carried by the busy slots' tiles, per GEMM
        CTRL_COLD2_SLOTS = 10,                      // cold slots with two fragments (33 .. kColdRows rows)
-       CTRL_WORK_GATEUP = 16, CTRL_WORK_DOWN = 24, // tile queue counters of the two GEMMs, one per XCD
-       CTRL_WORDS = 32 };
+       CTRL_WORK_GATEUP = 4, CTRL_WORK_DOWN = 5,   // dynamic tile counters of the two GEMMs
+       CTRL_WORDS = 16 };
 
 // A slot with at most this many rows is "cold": its tiles do next to no matrix work and are
 // bound by streaming the weights.  The packed FFN cuts their column tiles in half (twice as

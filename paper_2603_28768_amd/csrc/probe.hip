@@ -21,7 +21,10 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4_t *src, u32
 // can pull data out of L2; the XOR of everything read goes to `sink`.
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4_t *src, int64_t n, int passes, uint32_t *sink) {
     u32x4_t acc = {0u, 0u, 0u, 0u};
-    const int64_t start = ((int64_t)blockIdx.x * 2048) % n;
+    // workgroups that may share a compute unit (every 256th) start an eighth of the buffer apart,
+    // neighbours 8 KiB apart: no two of them walk the same lines at the same time, so the 32 KB
+    // L1 of a compute unit serves none of this
+    const int64_t start = ((int64_t)(blockIdx.x >> 8) * (n >> 3) + (int64_t)(blockIdx.x & 255) * 512) % n;
     for (int p = 0; p < passes; ++p)
         for (int64_t base = 0; base < n; base += 8 * 256) {
             u32x4_t v[8];

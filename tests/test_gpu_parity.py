@@ -40,6 +40,48 @@ def test_route_parity(torch_cuda, T, E, k, quantum, renorm):
     assert np.allclose(_np(w), rw, rtol=1e-5, atol=1e-30)
 
 
+def test_route_reads_scores_that_are_not_16_byte_aligned(torch_cuda):
+    # E % 4 == 0 lets the kernel read rows 16 bytes at a time, but only from a 16-byte aligned
+    # base: a score matrix that starts 4 bytes into an allocation is read score by score
+    torch = torch_cuda
+    T, E, k = 300, 128, 8
+    g = np.random.default_rng(77)
+    l = (g.standard_normal((T, E)) * 2).astype(np.float32)
+    flat = torch.empty(T * E + 1, dtype=torch.float32, device="cuda:0")
+    view = flat[1:].view(T, E)
+    view.copy_(torch.from_numpy(l))
+    assert view.data_ptr() % 16 == 4 and view.is_contiguous()
+    ids, w = binding.route_topk(view, k)
+    rid, rw = oracle.route(l, k)
+    assert np.array_equal(_np(ids), rid)
+    assert np.allclose(_np(w), rw, rtol=1e-5, atol=1e-30)
+
+
+# ---------------------------------------------------------------------- probes
+
+def test_measurement_probes(torch_cuda):
+    # the kernels of known work behind the benchmark's machine rates: the copy copies, the
+    # other two run and report the work they were asked for
+    torch = torch_cuda
+    g = torch.Generator(device="cuda").manual_seed(3)
+    a = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device="cuda:0", generator=g)
+    b = torch.zeros_like(a)
+    binding.probe_copy(a, b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    sink = torch.zeros(4 * 256, dtype=torch.float32, device="cuda:0")
+    assert binding.probe_mfma_bf16(10, sink, blocks=4) == 4 * 4 * 10 * 4 * 2 * 32 * 32 * 16
+    isink = torch.zeros(4 * 256, dtype=torch.int32, device="cuda:0")
+    small = torch.full((64 << 10,), 3, dtype=torch.uint8, device="cuda:0")
+    assert binding.probe_read(small, 3, isink, blocks=4) == 4 * 3 * (64 << 10)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
+    # every thread XORs the same number of equal words: an even count cancels
+    assert int(isink.abs().sum()) == 0
+    with pytest.raises(binding.CraftError):
+        binding.probe_read(small[:1000], 1, isink, blocks=4)          # not a multiple of 32 KiB
+
+
 # ------------------------------------------------------------------------ load
 
 @pytest.mark.parametrize("L,T,k,E,bt", [
