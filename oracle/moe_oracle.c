@@ -256,6 +256,7 @@ double oracle_e4m3_value(uint8_t code)
 int oracle_quantize_e4m3(const float *w, int64_t rows, int64_t K, uint8_t *codes, float *scale)
 {
     if (rows < 0 || K <= 0) return -1;
+#pragma omp parallel for schedule(static)              /* rows are independent of each other */
     for (int64_t r = 0; r < rows; ++r) {
         const float *row = w + r * K;
         float amax = 0.0f;
