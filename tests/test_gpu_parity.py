@@ -586,6 +586,24 @@ def test_cold_slots_riding_with_busy_tiles(torch_cuda, T, H, I, E, k, D, slots, 
             assert np.array_equal(outs[0], o)
 
 
+def test_block_ordered_tile_list_with_ragged_bands(torch_cuda):
+    # more than two rounds of busy tiles over the CUs: the kernels walk every slot's tiles block
+    # by block (bands of 8 row-tiles, blocks of 8 column tiles).  Four slots whose row-tile counts
+    # are no multiples of 8 and 10 column tiles per slot in both GEMMs give ragged last bands and
+    # a ragged last block of columns; every token is compared.
+    cfg = synth.scaled(synth.CONFIGS["qwen3"], T=16000, H=2560, I=1280, E=4, k=1, D=1, replica_slots=0,
+                       zipf_s=1.0, profile_batches=1)
+    case = Case(cfg)
+    rows = case.slot_cnt[case.rank_slot_off[0]:case.rank_slot_off[1]]
+    fwd, _, _ = case.gpu_rank(0, packed=True)
+    rg, rd, _, _ = fwd.tile_choice()
+    for height, nt in ((rg, (cfg.I + 127) // 128), (rd, (cfg.H + 255) // 256)):
+        row_tiles = [(int(r) + height - 1) // height for r in rows if r > 64]
+        assert sum(row_tiles) * nt > 2 * 256 and any(m % 8 for m in row_tiles) and nt % 8
+    print(f"  slot rows {rows.tolist()}, row-tiles of {rg}/{rd} rows", flush=True)
+    _check_rank(torch_cuda, case, 0, packed=True, cover=True)
+
+
 # -------------------------------------------------- full-size configurations
 
 @pytest.mark.parametrize("name", ["qwen3", "dsv3", "kimi"])
