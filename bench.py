@@ -460,6 +460,10 @@ def main():
                     help="run the FFN on row-major weights (LDS-staged kernels) instead of packed ones")
     ap.add_argument("--weights", default="bf16", choices=["bf16", "e4m3"],
                     help="storage of the packed expert weights: bf16, or E4M3 codes with a scale per row")
+    ap.add_argument("--tile-rows", type=int, nargs=2, default=[0, 0], metavar=("GATEUP", "DOWN"),
+                    help="row-tile heights of the two packed GEMMs (128..256 in steps of 32; 0 = the library's choice)")
+    ap.add_argument("--riders", type=int, nargs=2, default=[0, 0], metavar=("GATEUP", "DOWN"),
+                    help="cold slots riding on busy tiles: 1 on, -1 off, 0 = the library's choice")
     ap.add_argument("--timing-level", type=int, default=1,
                     help="inside the timed region: 1 = HIP events around the gate/up GEMM only, "
                          "2 = around every kernel (a second, untimed pass always brackets every kernel)")
@@ -492,6 +496,10 @@ def main():
         states = [setup(cfg, packed=packed, e4m3=e4m3)]
     cfg = states[0]["cfg"]
     packed = packed and cfg.dtype == "bf16"
+    for st in states:
+        fa = st["fwd"].args
+        fa.tile_rows_gateup, fa.tile_rows_down = args.tile_rows
+        fa.riders_gateup, fa.riders_down = args.riders
     for st in states:
         c = st["cfg"]
         log(f"config {c.name} layer {st['layer']}: T={c.T} H={c.H} I={c.I} E={c.E} k={c.k} D={c.D}; "
