@@ -205,7 +205,9 @@ craft_status craft_plan_diff(const craft_plan_t *old_plan, const craft_plan_t *n
  * forward given any other pointer returns CRAFT_EINVAL.  The copy is enqueued on `stream`
  * (no synchronisation) from pageable host memory that belongs to the plan, so the plan has to
  * outlive it; a forward enqueued later on the same stream sees the tables.  A buffer may be
- * filled again, also for another (layer, rank): it then counts for the last one only. */
+ * filled again, also for another (layer, rank): it then counts for the last one only.
+ * Uploads belong to set-up: the host memory is pageable, so do not record one into a stream
+ * capture. */
 craft_status craft_plan_tables_bytes(const craft_plan_t *plan, int32_t layer, int32_t rank,
                                      size_t *bytes);
 craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t rank,

@@ -341,17 +341,20 @@ craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t
         }
         std::lock_guard<std::mutex> lk(plan->reg_mutex);
         auto it = plan->reg_of.find(dev_tables);
-        if (it != plan->reg_of.end()) {
-            // the buffer held another rank's tables (or these): its old entry goes blank
+        const bool same = it != plan->reg_of.end() && it->second->layer == layer && it->second->rank == rank;
+        if (it != plan->reg_of.end() && !same) {
+            // the buffer held another rank's tables: its old entry goes blank
             it->second->dev.store(nullptr, std::memory_order_release);
             plan->reg_of.erase(it);
         }
         if (hipMemcpyAsync(dev_tables, rs.host_tables.data(), words * sizeof(int32_t), hipMemcpyHostToDevice,
                            as_stream(stream)) != hipSuccess)
             return CRAFT_EHIP;
-        craft_table_reg *n = new craft_table_reg{{dev_tables}, rs.regs.load(std::memory_order_relaxed)};
-        rs.regs.store(n, std::memory_order_release);
-        plan->reg_of.emplace(dev_tables, n);
+        if (!same) {
+            craft_table_reg *n = new craft_table_reg{{dev_tables}, rs.regs.load(std::memory_order_relaxed), layer, rank};
+            rs.regs.store(n, std::memory_order_release);
+            plan->reg_of.emplace(dev_tables, n);
+        }
     } catch (const std::bad_alloc &) {
         return CRAFT_ENOMEM;
     }

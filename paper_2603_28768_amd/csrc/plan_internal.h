@@ -29,6 +29,7 @@ struct craft_layer_plan {
 struct craft_table_reg {
     std::atomic<const void *> dev;
     craft_table_reg *next;
+    int32_t layer, rank;                  // whose list the node is in
 };
 
 // FFN tile choice made for one (T, k, H, I): for gate/up and down, the fragments per row-tile

@@ -524,6 +524,24 @@ def test_forward_rejects_foreign_tables(torch_cuda):
     fwd.args.tables = x.data_ptr()                                  # not a table buffer at all
     with pytest.raises(binding.CraftError):
         fwd(x, logits)
+    # a buffer filled again for another rank counts for that rank only; filled again for the
+    # same rank it stays good
+    import ctypes
+    mine = fwd.tables
+    n = ctypes.c_size_t()
+    lib = binding.lib()
+    assert lib.craft_plan_tables_bytes(case.plan._h, 0, 1, ctypes.byref(n)) == 0
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert lib.craft_plan_tables_upload(case.plan._h, 0, 1, ctypes.c_void_p(mine.data_ptr()), n.value, stream) == 0
+    fwd.args.tables = mine.data_ptr()
+    with pytest.raises(binding.CraftError):
+        fwd(x, logits)
+    for _ in range(2):
+        assert lib.craft_plan_tables_upload(case.plan._h, 0, 0, ctypes.c_void_p(mine.data_ptr()), n.value, stream) == 0
+    ref = case.oracle_rank(0)
+    out = fwd(x, logits)
+    torch.cuda.synchronize()
+    assert np.abs(_np(out).astype(np.float64) - ref["out"]).max() <= TOL[cfg.dtype] * np.abs(ref["out"]).max()
 
 
 def test_rank_with_more_slots_than_the_tile_tables_in_lds(torch_cuda):
