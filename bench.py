@@ -291,12 +291,12 @@ def copy_calibration(args):
 # (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
 # is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-_SHA = "f002a31210c4d959c2d6c28a5c6343b86a6f7245dfed4c68a00ec0087582de3f"
+_SHA = "5229c3f26574bd03f1fec1923f108f5662677bec5fbb3a9cc04ef6b8149a6252"
 TRAFFIC = {
-    "qwen3": dict(fetch_kib=290843.4, write_kib=15293.4, fetch_scale=2.0, write_scale=1.0, mfma_util=0.412, mfma_busy_of_peak_clock=0.353, l2_to_cu_mb=1284.1, l2_hit=0.549, sources_sha256=_SHA),
-    "dsv3": dict(fetch_kib=197901.1, write_kib=11777.2, fetch_scale=2.0, write_scale=1.0, mfma_util=0.517, mfma_busy_of_peak_clock=0.422, l2_to_cu_mb=1534.8, l2_hit=0.737, sources_sha256=_SHA),
-    "kimi": dict(fetch_kib=175629.4, write_kib=12171.8, fetch_scale=2.0, write_scale=1.0, mfma_util=0.495, mfma_busy_of_peak_clock=0.406, l2_to_cu_mb=1398.7, l2_hit=0.744, sources_sha256=_SHA),
-    "stack": dict(fetch_kib=984815.2, write_kib=84672.8, fetch_scale=2.0, write_scale=1.0, mfma_util=0.71, mfma_busy_of_peak_clock=0.505, l2_to_cu_mb=8847.0, l2_hit=0.779, sources_sha256=_SHA),
+    "qwen3": dict(fetch_kib=290426.4, write_kib=15273.3, fetch_scale=2.0, write_scale=1.0, mfma_util=0.407, mfma_busy_of_peak_clock=0.354, l2_to_cu_mb=1284.1, l2_hit=0.549, sources_sha256=_SHA),
+    "dsv3": dict(fetch_kib=198063.7, write_kib=11777.2, fetch_scale=2.0, write_scale=1.0, mfma_util=0.523, mfma_busy_of_peak_clock=0.429, l2_to_cu_mb=1534.9, l2_hit=0.736, sources_sha256=_SHA),
+    "kimi": dict(fetch_kib=175978.4, write_kib=12171.6, fetch_scale=2.0, write_scale=1.0, mfma_util=0.506, mfma_busy_of_peak_clock=0.416, l2_to_cu_mb=1398.7, l2_hit=0.744, sources_sha256=_SHA),
+    "stack": dict(fetch_kib=972059.0, write_kib=86118.2, fetch_scale=2.0, write_scale=1.0, mfma_util=0.708, mfma_busy_of_peak_clock=0.507, l2_to_cu_mb=8847.0, l2_hit=0.771, sources_sha256=_SHA),
 }
 
 
