@@ -66,8 +66,6 @@ typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 // (exactly) right in front of the MFMAs that use them.
 template <bool W8> struct WFrag { typedef bf16x8_t type; };
 template <> struct WFrag<true> { typedef u32x2_t type; };
-template <bool W8> struct WStream { typedef const bf16x8_t __attribute__((address_space(1))) *type; };
-template <> struct WStream<true> { typedef const u32x2_t __attribute__((address_space(1))) *type; };
 
 static __device__ __forceinline__ bf16x8_t widen(bf16x8_t w) { return w; }
 static __device__ __forceinline__ bf16x8_t widen(u32x2_t w) {
@@ -88,7 +86,18 @@ template <> __device__ __forceinline__ u32x2_t zero_fragment<true>() {
     const u32x2_t z = {0u, 0u};
     return z;
 }
-typedef const u32x4_t __attribute__((address_space(1))) *xchunk_t;
+// Every global load of the contraction loop is addressed as a wave-uniform 64-bit base (scalar
+// registers, advanced with scalar adds) plus a 32-bit byte offset per lane: no 64-bit vector
+// arithmetic per request, and half the address registers to hand to the memory pipeline.
+typedef const unsigned char *ubase_t;
+static __device__ __forceinline__ ubase_t uniform_base(const void *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<ubase_t>(((uint64_t)hi << 32) | lo);
+}
+static __device__ __forceinline__ u32x4_t xload(ubase_t base, uint32_t off) {
+    return *(const u32x4_t __attribute__((address_space(1))) *)(base + off);
+}
 // The lane's index inside its wave, counted afresh from the execution mask: with the wave's
 // index kept in a scalar register no vector register has to carry the thread index through
 // the contraction loops (it was spilled there, and its reload at the start of the epilogue
@@ -100,11 +109,27 @@ static __device__ __forceinline__ int lane_index() {
 }
 // A weight fragment that no other tile of the launch reads (a cold slot's: it has one
 // row-tile): a streaming load, which leaves the L2 to the weights and rows that are shared.
-template <bool ONCE, typename P>
-static __device__ __forceinline__ auto wload(P p) -> decltype(*p + *p) {
+template <bool ONCE, typename F>
+static __device__ __forceinline__ F wload(ubase_t base, uint32_t &off) {
+    // the lane's offset never changes inside a tile; widened to 64 bits once outside the loop it
+    // would no longer be recognised as the 32-bit offset of a scalar-base request
+    // (redefined in place, so that no copy is made)
+    asm volatile("" : "+v"(off));
+    const F __attribute__((address_space(1))) *p = (const F __attribute__((address_space(1))) *)(base + off);
     if (ONCE) return __builtin_nontemporal_load(p);
     return *p;
 }
+
+// Where a tile's operands come from.  The bases are wave-uniform; the weight offsets woff /
+// wroff are the ring's next refill (the step that many ahead, held at the last step of the
+// stream once it is reached) and move on by one step's worth of fragments per step.
+struct Streams {
+    ubase_t wb, wbr;           // packed weights of the tile's slot and of the rider's slot
+    uint32_t wl, wlr;          // the lane's place in a step: (first column group * 64 + lane) fragments, in bytes
+    uint32_t woff, wroff;      // running refill offsets, in bytes
+    uint32_t wstep, wlast;     // bytes per step; offset of the last step
+    ubase_t xb, xbr;           // activation rows of the tile and of the rider
+};
 
 // One 16-wide contraction step of NGT x NXF MFMAs (NGT column groups per wave).  A wave is alone on its SIMD, so whatever
 // it issues between two MFMAs delays the second one unless it fits into the 32 cycles the
@@ -122,18 +147,20 @@ static __device__ __forceinline__ auto wload(P p) -> decltype(*p + *p) {
 //                         MFMA at the end of the last group's, its LDS read behind that
 //                         group's first MFMA, its refill behind itself
 template <int NXF, int NGT, int R, int RR, int PW, int PHASE, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_step(const unsigned char *xnext, int step, int ksteps, typename WStream<W8>::type wp,
-                                            typename WStream<W8>::type wpr, int64_t wstride,
+__device__ __forceinline__ void packed_step(const unsigned char *xnext, Streams &sm,
                                             typename WFrag<W8>::type (&wq)[NGT][PW],
                                             typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
                                             const bf16x8_t (&XC)[NXF + RIDER], bf16x8_t (&XN)[NXF + RIDER],
                                             f32x16_t (&acc)[NGT][NXF], f32x16_t (&accr)[1][1], unsigned char *xstage,
-                                            u32x4_t (&XR)[NXF + RIDER], xchunk_t xin, const uint32_t (&xp)[NXF + RIDER],
-                                            int koff) {
+                                            u32x4_t (&XR)[NXF + RIDER], const uint32_t (&xp)[NXF + RIDER],
+                                            uint32_t koff) {
     static_assert(!RIDER || NGT >= 2, "a rider needs a group of its own to hide behind");
+    typedef typename WFrag<W8>::type F;
     constexpr int NXA = NXF + (RIDER ? 1 : 0);     // activation fragments in LDS, the rider's last
     constexpr int HALF = (NXA + 1) / 2;
-    const int64_t nxt = min(step + PW, ksteps - 1) * wstride;
+    sm.woff = min(sm.woff + sm.wstep, sm.wlast);
+    if (RIDER) sm.wroff = min(sm.wroff + sm.wstep, sm.wlast);
+    const ubase_t wcur = sm.wb + sm.woff, wrcur = sm.wbr + sm.wroff;
 #pragma unroll
     for (int n = 0; n < NGT; ++n) {
         const bool last = n == NGT - 1;
@@ -150,12 +177,12 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
                 const int i = PHASE * HALF + g / 2;
                 if (i < NXA && i < (PHASE + 1) * HALF) {
                     if ((g & 1) == 0) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
-                    if ((g & 1) == 1 || g == NXA - 1) XR[i] = xin[(size_t)xp[i] + koff];
+                    if ((g & 1) == 1 || g == NXA - 1) XR[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + koff);
                 }
             }
-            if (g == NXF - 1) wq[n][R] = wload<ONCE>(wp + nxt + n * 64);
+            if (g == NXF - 1) wq[n][R] = wload<ONCE, F>(wcur + n * 64 * (int)sizeof(F), sm.wl);
             if (RIDER && last && g == NXA - 1)
-                wr[RR % rider_ring(NXF, W8)] = wload<true>(wpr + min(step + rider_ring(NXF, W8), ksteps - 1) * wstride);
+                wr[RR % rider_ring(NXF, W8)] = wload<true, F>(wrcur, sm.wlr);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -168,25 +195,24 @@ __device__ __forceinline__ void packed_step(const unsigned char *xnext, int step
 // fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
 // enough: a stage is rewritten a full slab after its last reader has passed a barrier.
 template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_slab(int ks, int last_slab, int ksteps, int K, int kc, int lr,
+__device__ __forceinline__ void packed_slab(int ks, int last_slab, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
-                                            typename WStream<W8>::type wp, typename WStream<W8>::type wpr,
-                                            int64_t wstride, xchunk_t xin, const uint32_t (&xp)[NXF + RIDER],
+                                            Streams &sm, const uint32_t (&xp)[NXF + RIDER],
                                             typename WFrag<W8>::type (&wq)[NGT][PW],
                                             typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
                                             u32x4_t (&XR)[NXF + RIDER], bf16x8_t (&X0)[NXF + RIDER],
                                             bf16x8_t (&X1)[NXF + RIDER], f32x16_t (&acc)[NGT][NXF],
                                             f32x16_t (&accr)[1][1]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
-    // (in 16-byte chunks, like the row offsets xp)
-    const int koff = min(min(ks + 2, last_slab) * 64 + kc * 8, K - 8) >> 3;
+    // (in bytes, like the row offsets xp)
+    const uint32_t koff = (uint32_t)min(min(ks + 2, last_slab) * 128 + kc * 16, K * 2 - 16);
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER, ONCE>(xs + 32, ks * 4 + 0, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER, ONCE>(xs + 64, ks * 4 + 1, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER, ONCE>(xs + 32, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
     __syncthreads();
-    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER, ONCE>(xs + 96, ks * 4 + 2, ksteps, wp, wpr, wstride, wq, wr, X0, X1, acc, accr, xstage, XR, xin, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER, ONCE>(nxt + frag_off, ks * 4 + 3, ksteps, wp, wpr, wstride, wq, wr, X1, X0, acc, accr, xstage, XR, xin, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER, ONCE>(xs + 96, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
+    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER, ONCE>(nxt + frag_off, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
 }
 
 // Epilogue of NF accumulator fragments x NGT column groups, which are the rows of tile t from
@@ -207,34 +233,41 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
     const int lane = lane_index();
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
     const bool upper = lane >= 32;
+    constexpr int NVG = GATEUP ? 2 : 4;            // blocks of 8 output columns per group
+    // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows,
+    // then up rows; or down rows) and multiplies the accumulator of that output column.
+    // The scales depend on the column only: fetched once per group, not once per fragment.
+    float sa[NGT][NVG][4], sb[NGT][NVG][4];
 #pragma unroll
-    for (int n = 0; n < NGT; ++n) {
-        const int cbase = (group0 + n) * GC;
-        constexpr int NVG = GATEUP ? 2 : 4;        // blocks of 8 output columns per group
-        // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows,
-        // then up rows; or down rows) and multiplies the accumulator of that output column.
-        // The scales depend on the column only: fetched once per group, not once per fragment.
-        float sa[NVG][4], sb[NVG][4];
+    for (int n = 0; n < NGT; ++n)
 #pragma unroll
         for (int vg = 0; vg < NVG; ++vg)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) sa[vg][c] = sb[vg][c] = 1.0f;
-        if (W8) {
+            for (int c = 0; c < 4; ++c) sa[n][vg][c] = sb[n][vg][c] = 1.0f;
+    if (W8) {
+#pragma unroll
+        for (int n = 0; n < NGT; ++n)
 #pragma unroll
             for (int vg = 0; vg < NVG; ++vg) {
-                const int c0 = min(cbase + vg * 8 + (lane >> 5) * 4, N - 4);   // padding columns: any valid scale
+                const int c0 = min((group0 + n) * GC + vg * 8 + (lane >> 5) * 4, N - 4);   // padding columns: any valid scale
                 const float4 va = *reinterpret_cast<const float4 *>(wscale + c0);
-                sa[vg][0] = va.x; sa[vg][1] = va.y; sa[vg][2] = va.z; sa[vg][3] = va.w;
+                sa[n][vg][0] = va.x; sa[n][vg][1] = va.y; sa[n][vg][2] = va.z; sa[n][vg][3] = va.w;
                 if (GATEUP) {
                     const float4 vb = *reinterpret_cast<const float4 *>(wscale + N + c0);
-                    sb[vg][0] = vb.x; sb[vg][1] = vb.y; sb[vg][2] = vb.z; sb[vg][3] = vb.w;
+                    sb[n][vg][0] = vb.x; sb[n][vg][1] = vb.y; sb[n][vg][2] = vb.z; sb[n][vg][3] = vb.w;
                 }
             }
-        }
+    }
+    // Fragment by fragment, all column groups of the wave before the next fragment: the stores
+    // that fill one 128-byte line of an output row (a wave's 64 columns of the down GEMM) follow
+    // one another, so the line leaves the L2 whole instead of in pieces.
 #pragma unroll
-        for (int g = 0; g < NF; ++g) {
-            const int m = g * 32 + (lane & 31);
-            unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
+    for (int g = 0; g < NF; ++g) {
+        const int m = g * 32 + (lane & 31);
+        unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
+#pragma unroll
+        for (int n = 0; n < NGT; ++n) {
+            const int cbase = (group0 + n) * GC;
             // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
 #pragma unroll
             for (int vg = 0; vg < NVG; vg += 2) {
@@ -244,9 +277,9 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
                     float h[4];
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c] * sa[vg + b][c]) *
-                                            (acc[n][g][8 + (vg + b) * 4 + c] * sb[vg + b][c])
-                                      : acc[n][g][(vg + b) * 4 + c] * sa[vg + b][c];
+                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c] * sa[n][vg + b][c]) *
+                                            (acc[n][g][8 + (vg + b) * 4 + c] * sb[n][vg + b][c])
+                                      : acc[n][g][(vg + b) * 4 + c] * sa[n][vg + b][c];
                     piece[b][0] = bf16_pair(h[0], h[1]);
                     piece[b][1] = bf16_pair(h[2], h[3]);
                 }
@@ -289,20 +322,35 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
     // of a tile has a stream to read even past the last real column.
     const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
-    typename WStream<W8>::type wp = (typename WStream<W8>::type)wbase + (int64_t)group0 * 64 + lane;
-    typename WStream<W8>::type wpr = (typename WStream<W8>::type)wbase_r + (int64_t)group_r * 64 + lane;
-    const int64_t wstride = (int64_t)groups_padded * 64;
-    // activation rows as offsets in 16-byte chunks from the start of the matrix: 32 bits per
-    // row instead of a pointer (the host checks that the matrix has fewer than 2^32 chunks)
-    xchunk_t xin = (xchunk_t)(GATEUP ? a.x : a.act);
-    const uint32_t kchunks = (uint32_t)K >> 3;
+    typedef typename WFrag<W8>::type F;
+    Streams sm;
+    sm.wb = uniform_base(wbase);
+    sm.wbr = uniform_base(wbase_r);
+    sm.wl = (uint32_t)(group0 * 64 + lane) * (uint32_t)sizeof(F);
+    sm.wlr = (uint32_t)(group_r * 64 + lane) * (uint32_t)sizeof(F);
+    sm.wstep = (uint32_t)groups_padded * 64u * (uint32_t)sizeof(F);
+    sm.wlast = (uint32_t)(ksteps - 1) * sm.wstep;  // the host checks that a packed matrix stays below 4 GiB
+    sm.woff = (uint32_t)(PW - 1) * sm.wstep;       // the loop's first refill is step PW (ksteps >= 16 >= PW)
+    sm.wroff = (uint32_t)(rider_ring(NXF, W8) - 1) * sm.wstep;
+    // Activation rows as 32-bit byte offsets from a uniform base.  Gate/up gathers token rows
+    // from all over x (the host checks that x stays below 4 GiB); the down GEMM's rows follow
+    // one another from the tile's first row on, the rider's from the rider's first row.
+    const uint32_t row_bytes = (uint32_t)K * 2u;
+    if (GATEUP) {
+        sm.xb = sm.xbr = static_cast<ubase_t>(a.x);
+    } else {
+        const int32_t row0 = __builtin_amdgcn_readfirstlane(t.pos0 + t.m0 - lo_pos);
+        const int32_t row0r = __builtin_amdgcn_readfirstlane(r.pos0 + r.m0 - lo_pos);
+        sm.xb = static_cast<ubase_t>(a.act) + (int64_t)row0 * row_bytes;
+        sm.xbr = static_cast<ubase_t>(a.act) + (int64_t)row0r * row_bytes;
+    }
     uint32_t xp[NXA];
 #pragma unroll
     for (int i = 0; i < NXA; ++i) {
         const bool own = i < NXF;
         const int rr = own ? min(lr + 32 * i, t.rows - 1) : min(lr, r.rows - 1);
         const int32_t pos = own ? t.pos0 + t.m0 + rr : r.pos0 + r.m0 + rr;
-        xp[i] = (uint32_t)(GATEUP ? a.src[pos] / a.k : pos - lo_pos) * kchunks;
+        xp[i] = (uint32_t)(GATEUP ? a.src[pos] / a.k : rr) * row_bytes;
     }
 
     f32x16_t acc[NGT][NXF], accr[1][1];
@@ -325,24 +373,24 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 #pragma unroll
         for (int j = 0; j < PW / 2; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE>(wp + j * wstride + n * 64);
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + n * 64 * (int)sizeof(F), sm.wl);
         if (RIDER)
 #pragma unroll
-            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wload<true>(wpr + j * wstride);
+            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep, sm.wlr);
         if (!RIDER) wr[0] = zero_fragment<W8>();    // a placeholder that no MFMA reads
-        const int k0 = min(kc * 8, K - 8) >> 3, k1 = min(64 + kc * 8, K - 8) >> 3;
+        const uint32_t k0 = (uint32_t)min(kc * 16, K * 2 - 16), k1 = (uint32_t)min(128 + kc * 16, K * 2 - 16);
 #pragma unroll
-        for (int i = 0; i < NXA; ++i) xfirst[i] = xin[(size_t)xp[i] + k0];
+        for (int i = 0; i < NXA; ++i) xfirst[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + k0);
 #pragma unroll
-        for (int i = 0; i < NXA; ++i) xr[i] = xin[(size_t)xp[i] + k1];
+        for (int i = 0; i < NXA; ++i) xr[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + k1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = PW / 2; j < PW; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE>(wp + j * wstride + n * 64);
+            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + n * 64 * (int)sizeof(F), sm.wl);
         if (RIDER)
 #pragma unroll
-            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wload<true>(wpr + j * wstride);
+            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep, sm.wlr);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NXA; ++i)
@@ -355,16 +403,17 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     for (int g = 0; g < NXA; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 32 * XROWB);
 
     const int last_slab = nk4 * 4 - 1;
-    int st = 0;                                    // LDS stage of the current slab
+    // the three LDS stages, s0 the one of the current slab: four slabs on, the roles have moved by one
+    unsigned char *s0 = smem, *s1 = smem + XSTAGEB, *s2 = smem + 2 * XSTAGEB;
     for (int ks = 0; ks <= last_slab; ks += 4) {
-        unsigned char *s0 = smem + st * XSTAGEB;
-        unsigned char *s1 = smem + (st + 1) % 3 * XSTAGEB;
-        unsigned char *s2 = smem + (st + 2) % 3 * XSTAGEB;
-        packed_slab<NXF, NGT, 0, PW, W8, RIDER, ONCE>(ks + 0, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 1, PW, W8, RIDER, ONCE>(ks + 1, last_slab, ksteps, K, kc, lr, s1, s2, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 2, PW, W8, RIDER, ONCE>(ks + 2, last_slab, ksteps, K, kc, lr, s2, s0, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 3, PW, W8, RIDER, ONCE>(ks + 3, last_slab, ksteps, K, kc, lr, s0, s1, frag_off, wp, wpr, wstride, xin, xp, wq, wr, xr, x0, x1, acc, accr);
-        st = (st + 1) % 3;
+        packed_slab<NXF, NGT, 0, PW, W8, RIDER, ONCE>(ks + 0, last_slab, K, kc, lr, s0, s1, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 1, PW, W8, RIDER, ONCE>(ks + 1, last_slab, K, kc, lr, s1, s2, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 2, PW, W8, RIDER, ONCE>(ks + 2, last_slab, K, kc, lr, s2, s0, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 3, PW, W8, RIDER, ONCE>(ks + 3, last_slab, K, kc, lr, s0, s1, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
+        unsigned char *const s3 = s0;
+        s0 = s1;
+        s1 = s2;
+        s2 = s3;
     }
 
     // The next work item is claimed before the epilogue and looked at after it: the counter's

@@ -485,10 +485,15 @@ craft_status forward_on(const craft_plan_t *plan, int32_t layer, int32_t rank, c
         if (a->weight_format != CRAFT_W_BF16 && a->weight_format != CRAFT_W_E4M3) return CRAFT_EINVAL;
         if (a->weight_format == CRAFT_W_E4M3 && !packed) return CRAFT_EINVAL;
         if (nslots > 0 && !packed && (!a->w_gate || !a->w_up || !a->w_down)) return CRAFT_EINVAL;
-        // the packed kernels address activation rows by 32-bit offsets in 16-byte chunks
-        const int64_t chunk_limit = (int64_t)1 << 32;
-        if (packed && (a->T * (int64_t)a->H / 8 >= chunk_limit || L.max_rows * (int64_t)a->I / 8 >= chunk_limit))
-            return CRAFT_EINVAL;
+        // the packed kernels address token rows of x and the fragments of one packed matrix by
+        // 32-bit byte offsets from a base
+        if (packed) {
+            const int64_t limit = (int64_t)1 << 32;
+            size_t gub = 0, dnb = 0;
+            if (a->weight_format == CRAFT_W_E4M3) packed_sizes_e4m3(a->H, a->I, &gub, &dnb);
+            else packed_sizes(a->H, a->I, &gub, &dnb);
+            if (a->T * (int64_t)a->H * 2 >= limit || (int64_t)gub >= limit || (int64_t)dnb >= limit) return CRAFT_EINVAL;
+        }
     }
     hipStream_t s = as_stream(stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
