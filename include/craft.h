@@ -215,9 +215,10 @@ craft_status craft_plan_tables_upload(craft_plan_t *plan, int32_t layer, int32_t
 
 /* --------------------------------------------------------------- weight packing
  * One-time re-ordering of one expert's bf16 weights into the order the grouped-GEMM
- * kernels stream them in (MFMA operand fragments: 64 lanes x 16 bytes per 32-row x
- * 16-element block; gate and up rows of the same output columns interleaved 16 + 16;
- * rows and contraction padded with zeros to whole blocks).  It belongs to model loading,
+ * kernels stream them in (MFMA operand fragments: 64 lanes x 16 bytes per 16-row x
+ * 32-element block; the 16 gate rows of a group of output columns followed by the 16 up
+ * rows of the same columns; rows and contraction padded with zeros to whole blocks).  It
+ * belongs to model loading,
  * like placing the weights in HBM, and is not part of a forward.
  *   w_gate, w_up  DEVICE [I][H] bf16;  w_down DEVICE [H][I] bf16 (Sec. 2.1: up-projection,
  *                 non-linearity, down-projection)

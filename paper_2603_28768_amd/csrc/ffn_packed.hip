@@ -49,13 +49,13 @@
 namespace craft {
 namespace {
 
-// Weight steps kept in flight per column group: deep for the streaming-bound tiles with few
-// row fragments, shallower where the accumulators need the registers and each step carries
+// 32-wide weight steps kept in flight per column group: deep for the streaming-bound tiles with
+// few row fragments, shallower where the accumulators need the registers and each step carries
 // enough MFMA work to cover the latency.
-constexpr int ring_depth(int nxa) { return nxa >= 3 ? 8 : 16; }
+constexpr int ring_depth(int nxa) { return nxa >= 3 ? 4 : 8; }
 // The rider's weights always come from HBM (nobody else reads them): where the registers are
 // there its ring runs twice as far ahead as the tile's own.
-constexpr int rider_ring(int nxf, bool w8) { return w8 || nxf <= 4 ? 16 : 8; }
+constexpr int rider_ring(int nxf, bool w8) { return w8 || nxf <= 4 ? 8 : 4; }
 constexpr int NG = 2;             // column groups per wave in a full-width tile (1 in a half-width one)
 constexpr int kPackGroups = 8;    // the packed stream is padded to whole full-width tiles
 constexpr int XROWB = 64 * 2 + 16;
@@ -125,106 +125,166 @@ static __device__ __forceinline__ F wload(ubase_t base, uint32_t &off) {
 // stream once it is reached) and move on by one step's worth of fragments per step.
 struct Streams {
     ubase_t wb, wbr;           // packed weights of the tile's slot and of the rider's slot
-    uint32_t wl, wlr;          // the lane's place in a step: (first column group * 64 + lane) fragments, in bytes
+    uint32_t wl, wlr;          // the lane's place in a step: (first fragment * 64 + lane) fragments, in bytes
     uint32_t woff, wroff;      // running refill offsets, in bytes
     uint32_t wstep, wlast;     // bytes per step; offset of the last step
     ubase_t xb, xbr;           // activation rows of the tile and of the rider
 };
 
-// One 16-wide contraction step of NGT x NXF MFMAs (NGT column groups per wave).  A wave is alone on its SIMD, so whatever
-// it issues between two MFMAs delays the second one unless it fits into the 32 cycles the
-// first one keeps the matrix pipeline busy: memory operations are therefore dealt out one or
-// two per MFMA, and a scheduling barrier after each MFMA pins that order.
-//   MFMA j < NXF        : + LDS read of fragment j of the FOLLOWING step into XN (a whole step
-//                         of matrix work covers its latency; this step runs on XC)
-//   last group's MFMAs  : + (PHASE 0/1, the first two steps of a slab) an activation row chunk
-//                         of the next slab goes from XR to LDS stage `nxt` behind one MFMA, and
-//                         the same registers are requested again for the slab after it behind
-//                         the next MFMA
-//   a group's last MFMA : + refill of the weight ring slot that group has just used
-//   the rider, if any   : fragment NXF of the activations belongs to a cold slot and meets one
-//                         column group of that slot's weights (a ring of its own): one more
-//                         MFMA at the end of the last group's, its LDS read behind that
-//                         group's first MFMA, its refill behind itself
-template <int NXF, int NGT, int R, int RR, int PW, int PHASE, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_step(const unsigned char *xnext, Streams &sm,
-                                            typename WFrag<W8>::type (&wq)[NGT][PW],
-                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
+// acc += w x^T for a 16-row weight fragment and a 16-row activation fragment over 32
+// contraction elements.  Written out as an instruction whose accumulator operand is both read
+// and written (an accumulation register tuple, "+a"): a tall tile's 64 accumulators fill the
+// accumulation half of the register file exactly, and every copy the register allocator makes
+// when result and addend are two values costs moves through the other half.  The compiler does
+// not know that this is a matrix instruction: the waits it would insert between a matrix
+// instruction and a read of its result are the caller's (settle_accumulators) — inside the
+// contraction loop an accumulator is touched again only a whole half-step later.
+// FRESH: an operand has just been written by ordinary vector instructions (8-bit weights
+// widened to bf16); a matrix instruction may read such a register two issue cycles later at
+// the earliest, which the compiler would see to for an instruction it knows.
+template <bool FRESH>
+static __device__ __forceinline__ void mfma16(bf16x8_t w, bf16x8_t x, f32x4_t &c) {
+    if (FRESH) asm("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(w), "v"(x));
+    else asm("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(w), "v"(x));
+}
+// After the last matrix instruction and before the first ordinary read of an accumulator: more
+// idle issue cycles than the longest wait the hardware asks for between the two.  Every
+// accumulator then passes through an empty statement that is ordered behind the idle cycles
+// (both are volatile), so that no read of it can be scheduled ahead of them.
+template <int NGT, int NXF>
+static __device__ __forceinline__ void settle_accumulators(f32x4_t (&acc)[NGT][2][2 * NXF], f32x4_t (&accr)[1][2][2],
+                                                           bool rider) {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int n = 0; n < NGT; ++n)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int g = 0; g < 2 * NXF; ++g) asm volatile("" : "+a"(acc[n][h][g]));
+    if (rider)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) asm volatile("" : "+a"(accr[0][h][i]));
+}
+
+// Half of one 32-wide contraction step: the step's 2 NGT weight fragments (NGT column groups per
+// wave, two 16-row fragments each) against the lower (HI = 0) or upper (HI = 1) NXF 16-row
+// activation fragments of the tile, 2 NGT NXF MFMAs of 16 cycles.  A wave is alone on its SIMD,
+// so whatever it issues between two MFMAs delays the second one unless it fits into the cycles
+// the first one keeps the matrix pipeline busy: memory operations are therefore dealt out one
+// per MFMA, and a scheduling barrier after each MFMA pins that order.
+//   MFMA m < NXF           : + LDS read of fragment m of the FOLLOWING half-step into XN (this
+//                            one runs on XC; a whole half-step of matrix work covers the latency)
+//   the last MFMAs, STAGE  : the lower half-steps of a slab move the activation rows of the next
+//   0 / 1                    slab from XR to LDS stage `nxt` (first / second half of the row
+//                            chunks), a chunk's LDS write behind one MFMA, the request that
+//                            refills its registers for the slab after that behind the next
+//   HI, a fragment's last  : + refill of the ring slot that weight fragment came from
+//   the rider, if any      : fragment NXF of the activations is 16 rows of a cold slot (its lower
+//                            16 in the lower half-step) and meets one column group of that
+//                            slot's weights (a ring of its own): two more MFMAs at the end
+template <int NXF, int NGT, int R, int RR, int PW, int HI, int STAGE, bool W8, bool RIDER, bool ONCE>
+__device__ __forceinline__ void packed_half(const unsigned char *xnext, Streams &sm,
+                                            typename WFrag<W8>::type (&wq)[NGT][PW][2],
+                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1][2],
                                             const bf16x8_t (&XC)[NXF + RIDER], bf16x8_t (&XN)[NXF + RIDER],
-                                            f32x16_t (&acc)[NGT][NXF], f32x16_t (&accr)[1][1], unsigned char *xstage,
+                                            f32x4_t (&acc)[NGT][2][2 * NXF], f32x4_t (&accr)[1][2][2], unsigned char *xstage,
                                             u32x4_t (&XR)[NXF + RIDER], const uint32_t (&xp)[NXF + RIDER],
                                             uint32_t koff) {
-    static_assert(!RIDER || NGT >= 2, "a rider needs a group of its own to hide behind");
     typedef typename WFrag<W8>::type F;
-    constexpr int NXA = NXF + (RIDER ? 1 : 0);     // activation fragments in LDS, the rider's last
+    constexpr int NXA = NXF + (RIDER ? 1 : 0);     // activation fragments of a half in LDS, the rider's last
     constexpr int HALF = (NXA + 1) / 2;
-    sm.woff = min(sm.woff + sm.wstep, sm.wlast);
-    if (RIDER) sm.wroff = min(sm.wroff + sm.wstep, sm.wlast);
+    constexpr int M = 2 * NGT * NXF + (RIDER ? 2 : 0);                 // MFMAs of this half-step
+    constexpr int C0 = STAGE < 0 ? 0 : STAGE * HALF;                   // row chunks staged here: C0 .. C1 - 1
+    constexpr int C1 = STAGE < 0 ? 0 : (NXA < (STAGE + 1) * HALF ? NXA : (STAGE + 1) * HALF);
+    constexpr int OP0 = M - 2 * (C1 - C0) > 0 ? M - 2 * (C1 - C0) : 0; // MFMA behind which the first staging operation goes
+    constexpr int NH = 1 - HI;                     // the half that is fetched from LDS meanwhile
+    constexpr int RING_R = rider_ring(NXF, W8);
+    if (HI) {
+        sm.woff = min(sm.woff + sm.wstep, sm.wlast);
+        if (RIDER) sm.wroff = min(sm.wroff + sm.wstep, sm.wlast);
+    }
     const ubase_t wcur = sm.wb + sm.woff, wrcur = sm.wbr + sm.wroff;
+    // what follows MFMA m
+    auto after = [&](int m) __attribute__((always_inline)) {
+        if (m < NXF) XN[m] = *reinterpret_cast<const bf16x8_t *>(xnext + 16 * (NH * NXF + m) * XROWB);
+        if (RIDER && m == NXF) XN[NXA - 1] = *reinterpret_cast<const bf16x8_t *>(xnext + (32 * NXF + 16 * NH) * XROWB);
+#pragma unroll
+        for (int i = C0; i < C1; ++i) {
+            const int w_at = OP0 + 2 * (i - C0) < M - 1 ? OP0 + 2 * (i - C0) : M - 1;
+            const int r_at = OP0 + 2 * (i - C0) + 1 < M - 1 ? OP0 + 2 * (i - C0) + 1 : M - 1;
+            if (m == w_at) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
+            if (m == r_at) XR[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + koff);
+        }
+    };
 #pragma unroll
     for (int n = 0; n < NGT; ++n) {
-        const bool last = n == NGT - 1;
-        const bf16x8_t wf = widen(wq[n][R]);
 #pragma unroll
-        for (int g = 0; g < NXA; ++g) {
-            if (g < NXF) acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, XC[g], acc[n][g], 0, 0, 0);
-            else if (last) accr[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(widen(wr[RIDER ? RR % rider_ring(NXF, W8) : 0]), XC[g], accr[0][0], 0, 0, 0);
-            else continue;
-            if (n == 0 && g < NXF) XN[g] = *reinterpret_cast<const bf16x8_t *>(xnext + g * 32 * XROWB);
-            if (RIDER && last && g == 0) XN[NXF] = *reinterpret_cast<const bf16x8_t *>(xnext + NXF * 32 * XROWB);
-            if (last && PHASE < 2) {
-                // chunk i: its LDS write behind an even MFMA, its new request behind the next one
-                const int i = PHASE * HALF + g / 2;
-                if (i < NXA && i < (PHASE + 1) * HALF) {
-                    if ((g & 1) == 0) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
-                    if ((g & 1) == 1 || g == NXA - 1) XR[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + koff);
-                }
+        for (int h = 0; h < 2; ++h) {
+            const bf16x8_t wf = widen(wq[n][R][h]);
+#pragma unroll
+            for (int g = 0; g < NXF; ++g) {
+                if (g == 0) mfma16<W8>(wf, XC[g], acc[n][h][HI * NXF + g]);
+                else mfma16<false>(wf, XC[g], acc[n][h][HI * NXF + g]);
+                after((2 * n + h) * NXF + g);
+                if (HI && g == NXF - 1) wq[n][R][h] = wload<ONCE, F>(wcur + (2 * n + h) * 64 * (int)sizeof(F), sm.wl);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (g == NXF - 1) wq[n][R] = wload<ONCE, F>(wcur + n * 64 * (int)sizeof(F), sm.wl);
-            if (RIDER && last && g == NXA - 1)
-                wr[RR % rider_ring(NXF, W8)] = wload<true, F>(wrcur, sm.wlr);
+        }
+    }
+    if (RIDER) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            mfma16<W8>(widen(wr[RR % RING_R][h]), XC[NXA - 1], accr[0][h][HI]);
+            after(2 * NGT * NXF + h);
+            if (HI) wr[RR % RING_R][h] = wload<true, F>(wrcur + h * 64 * (int)sizeof(F), sm.wlr);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-// One 64-wide slab U (0..3) of a group of four.  On entry LDS stage `cur` holds this slab,
-// XR the next slab (in registers, requested one slab ago) and X0 the fragments of this
-// slab's first step.  During the first two steps XR goes into stage `nxt` and the slab two
-// ahead is requested from global memory into the same registers; the last step already
-// fetches the first fragments of the next slab.  Three LDS stages make one barrier per slab
-// enough: a stage is rewritten a full slab after its last reader has passed a barrier.
+// One 64-wide slab U (0..3) of a group of four: two 32-wide steps, four half-steps.  On entry
+// LDS stage `cur` holds this slab, XR the next slab (in registers, requested one slab ago) and
+// X0 the lower fragments of this slab's first step.  During the two lower half-steps XR goes
+// into stage `nxt` and the slab two ahead is requested from global memory into the same
+// registers; the last half-step already fetches the first fragments of the next slab.  Three
+// LDS stages make one barrier per slab enough: a stage is rewritten a full slab after its last
+// reader has passed a barrier.
 template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER, bool ONCE>
 __device__ __forceinline__ void packed_slab(int ks, int last_slab, int K, int kc, int lr,
                                             const unsigned char *cur, unsigned char *nxt, int frag_off,
                                             Streams &sm, const uint32_t (&xp)[NXF + RIDER],
-                                            typename WFrag<W8>::type (&wq)[NGT][PW],
-                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1],
+                                            typename WFrag<W8>::type (&wq)[NGT][PW][2],
+                                            typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1][2],
                                             u32x4_t (&XR)[NXF + RIDER], bf16x8_t (&X0)[NXF + RIDER],
-                                            bf16x8_t (&X1)[NXF + RIDER], f32x16_t (&acc)[NGT][NXF],
-                                            f32x16_t (&accr)[1][1]) {
+                                            bf16x8_t (&X1)[NXF + RIDER], f32x4_t (&acc)[NGT][2][2 * NXF],
+                                            f32x4_t (&accr)[1][2][2]) {
     // contraction offsets past the row are clamped into it: the weights there are zero
     // (in bytes, like the row offsets xp)
     const uint32_t koff = (uint32_t)min(min(ks + 2, last_slab) * 128 + kc * 16, K * 2 - 16);
     unsigned char *xstage = nxt + lr * XROWB + kc * 16;
     const unsigned char *xs = cur + frag_off;
-    packed_step<NXF, NGT, (U * 4 + 0) % PW, U * 4 + 0, PW, 0, W8, RIDER, ONCE>(xs + 32, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 1) % PW, U * 4 + 1, PW, 1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 0, 0, W8, RIDER, ONCE>(xs, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 1, -1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 0, 1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
     __syncthreads();
-    packed_step<NXF, NGT, (U * 4 + 2) % PW, U * 4 + 2, PW, 2, W8, RIDER, ONCE>(xs + 96, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
-    packed_step<NXF, NGT, (U * 4 + 3) % PW, U * 4 + 3, PW, 2, W8, RIDER, ONCE>(nxt + frag_off, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 1, -1, W8, RIDER, ONCE>(nxt + frag_off, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
 }
 
-// Epilogue of NF accumulator fragments x NGT column groups, which are the rows of tile t from
-// its first on and the groups from group0 on.  Accumulator element v of lane l belongs to
-// weight row (v/4)*8 + (l>>5)*4 + v%4 of the group and activation row (l & 31) of the
-// fragment: for each block vg of 8 output columns a lane holds 4 of them and lane l ^ 32 the
-// other 4 of the same row.  Two blocks at a time, the halves of the wave trade pieces
-// (v_permlane32_swap: the upper half of the first operand against the lower half of the
-// second), after which the lower half owns all 8 columns of the first block and the upper
-// half those of the second: 16-byte stores, half as many as 8-byte ones would be.
+// Epilogue of 2 NF accumulator fragments of 16 rows x NGT column groups, which are the rows of
+// tile t from its first on and the groups from group0 on.  Accumulator element v of lane l
+// belongs to weight row 4 (l >> 4) + v of its 16-row weight fragment and activation row
+// (l & 15) of its fragment: a lane holds 4 neighbouring output columns of one row, the lanes 16
+// further on the next 4.  Two fragments at a time, neighbouring quarters of the wave trade
+// pieces (v_permlane16_swap: the odd quarters of the first operand against the even quarters
+// of the second), after which every lane owns 8 neighbouring columns of one of the two: 16-byte
+// stores, half as many as 8-byte ones would be.  The two fragments are the two halves of a
+// 32-column group (down), the same rows of two neighbouring 16-column groups (gate/up, after
+// SwiGLU of the gate fragment with the up fragment of the same columns), or, where a wave has a
+// single group, two fragments of rows.
 template <bool GATEUP, int NGT, int NF, bool W8>
-__device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t, const f32x16_t (&acc)[NGT][NF],
+__device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t, const f32x4_t (&acc)[NGT][2][2 * NF],
                                                 const float *wscale, int group0, int N, int32_t lo_pos) {
     constexpr int GC = GATEUP ? 16 : 32;
     // the lane's row and column offsets are derived here, after the contraction loop: shared
@@ -232,73 +292,86 @@ __device__ __forceinline__ void store_fragments(const FfnArgs &a, const Tile &t,
     // would wait for the stores issued so far (loads and stores share one counter)
     const int lane = lane_index();
     unsigned short *outp = static_cast<unsigned short *>(GATEUP ? a.act : a.y);
-    const bool upper = lane >= 32;
-    constexpr int NVG = GATEUP ? 2 : 4;            // blocks of 8 output columns per group
+    const int q = lane >> 4;
     // E4M3 weights: the fp32 scale of every weight row sits behind the stream (gate rows,
     // then up rows; or down rows) and multiplies the accumulator of that output column.
     // The scales depend on the column only: fetched once per group, not once per fragment.
-    float sa[NGT][NVG][4], sb[NGT][NVG][4];
+    // sc[n][h]: gate/up h = 0 gate, 1 up (columns 16 (group0 + n) + 4 q ..); down h = half of the group
+    float sc[NGT][2][4];
 #pragma unroll
     for (int n = 0; n < NGT; ++n)
 #pragma unroll
-        for (int vg = 0; vg < NVG; ++vg)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) sa[n][vg][c] = sb[n][vg][c] = 1.0f;
+            for (int c = 0; c < 4; ++c) sc[n][h][c] = 1.0f;
     if (W8) {
 #pragma unroll
         for (int n = 0; n < NGT; ++n)
 #pragma unroll
-            for (int vg = 0; vg < NVG; ++vg) {
-                const int c0 = min((group0 + n) * GC + vg * 8 + (lane >> 5) * 4, N - 4);   // padding columns: any valid scale
-                const float4 va = *reinterpret_cast<const float4 *>(wscale + c0);
-                sa[n][vg][0] = va.x; sa[n][vg][1] = va.y; sa[n][vg][2] = va.z; sa[n][vg][3] = va.w;
-                if (GATEUP) {
-                    const float4 vb = *reinterpret_cast<const float4 *>(wscale + N + c0);
-                    sb[n][vg][0] = vb.x; sb[n][vg][1] = vb.y; sb[n][vg][2] = vb.z; sb[n][vg][3] = vb.w;
-                }
+            for (int h = 0; h < 2; ++h) {
+                const int c0 = min((group0 + n) * GC + (GATEUP ? 0 : 16 * h) + q * 4, N - 4);   // padding columns: any valid scale
+                const float4 v = *reinterpret_cast<const float4 *>(wscale + (GATEUP ? h * N : 0) + c0);
+                sc[n][h][0] = v.x; sc[n][h][1] = v.y; sc[n][h][2] = v.z; sc[n][h][3] = v.w;
             }
     }
+    // the lane's 4 columns of fragment f, group n (down: half h of it), as two packed pairs
+    auto piece = [&](int n, int h, int f, uint32_t (&p)[2]) __attribute__((always_inline)) {
+        float v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            v[c] = GATEUP ? silu_fast(acc[n][0][f][c] * sc[n][0][c]) * (acc[n][1][f][c] * sc[n][1][c])
+                          : acc[n][h][f][c] * sc[n][h][c];
+        p[0] = bf16_pair(v[0], v[1]);
+        p[1] = bf16_pair(v[2], v[3]);
+    };
+    // x, y: the pieces of the first and second fragment of a pair; afterwards quarter q of the
+    // wave holds columns 8 (q >> 1) .. + 7 of the first (q even) or second (q odd) fragment
+    auto trade_and_store = [&](const uint32_t (&x)[2], const uint32_t (&y)[2], int m, int col) __attribute__((always_inline)) {
+        const auto s0 = __builtin_amdgcn_permlane16_swap(x[0], y[0], false, false);
+        const auto s1 = __builtin_amdgcn_permlane16_swap(x[1], y[1], false, false);
+        if (m < t.rows && col < N) {
+            u32x4_t v;
+            v[0] = s0[0]; v[1] = s1[0]; v[2] = s0[1]; v[3] = s1[1];
+            unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + m - lo_pos) * N;
+            *reinterpret_cast<u32x4_t *>(orow + col) = v;
+        }
+    };
     // Fragment by fragment, all column groups of the wave before the next fragment: the stores
     // that fill one 128-byte line of an output row (a wave's 64 columns of the down GEMM) follow
     // one another, so the line leaves the L2 whole instead of in pieces.
+    if (!GATEUP) {
 #pragma unroll
-    for (int g = 0; g < NF; ++g) {
-        const int m = g * 32 + (lane & 31);
-        unsigned short *orow = outp + (int64_t)(t.pos0 + t.m0 + min(m, t.rows - 1) - lo_pos) * N;
+        for (int f = 0; f < 2 * NF; ++f)
 #pragma unroll
-        for (int n = 0; n < NGT; ++n) {
-            const int cbase = (group0 + n) * GC;
-            // gate/up: rows 0..15 of the group are gate, 16..31 the matching up rows
-#pragma unroll
-            for (int vg = 0; vg < NVG; vg += 2) {
-                uint32_t piece[2][2];
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    float h[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        h[c] = GATEUP ? silu_fast(acc[n][g][(vg + b) * 4 + c] * sa[n][vg + b][c]) *
-                                            (acc[n][g][8 + (vg + b) * 4 + c] * sb[n][vg + b][c])
-                                      : acc[n][g][(vg + b) * 4 + c] * sa[n][vg + b][c];
-                    piece[b][0] = bf16_pair(h[0], h[1]);
-                    piece[b][1] = bf16_pair(h[2], h[3]);
-                }
-                const auto s0 = __builtin_amdgcn_permlane32_swap(piece[0][0], piece[1][0], false, false);
-                const auto s1 = __builtin_amdgcn_permlane32_swap(piece[0][1], piece[1][1], false, false);
-                const int col = cbase + (vg + (upper ? 1 : 0)) * 8;
-                if (m < t.rows && col < N) {
-                    u32x4_t v;
-                    v[0] = s0[0]; v[1] = s1[0]; v[2] = s0[1]; v[3] = s1[1];
-                    *reinterpret_cast<u32x4_t *>(orow + col) = v;
-                }
+            for (int n = 0; n < NGT; ++n) {
+                uint32_t x[2], y[2];
+                piece(n, 0, f, x);
+                piece(n, 1, f, y);
+                trade_and_store(x, y, f * 16 + (lane & 15), (group0 + n) * GC + (q & 1) * 16 + (q >> 1) * 8);
             }
+    } else if (NGT == 2) {
+#pragma unroll
+        for (int f = 0; f < 2 * NF; ++f) {
+            uint32_t x[2], y[2];
+            piece(0, 0, f, x);
+            piece(NGT - 1, 0, f, y);
+            trade_and_store(x, y, f * 16 + (lane & 15), (group0 + (q & 1)) * GC + (q >> 1) * 8);
+        }
+    } else {
+#pragma unroll
+        for (int f = 0; f < 2 * NF; f += 2) {
+            uint32_t x[2], y[2];
+            piece(0, 0, f, x);
+            piece(0, 0, f + 1, y);
+            trade_and_store(x, y, (f + (q & 1)) * 16 + (lane & 15), group0 * GC + (q >> 1) * 8);
         }
     }
 }
 
-// One tile with NXF live 32-row activation fragments of its own slot and, with RIDER, one more
-// fragment of a cold slot (tile r: up to 32 rows, half a column tile starting at r.n0) that
-// meets one column group of that slot's weights per wave.
+// One tile with NXF live 32-row activation fragments of its own slot (2 NXF fragments of 16
+// rows: NXF lower, NXF upper) and, with RIDER, one more 32-row fragment of a cold slot (tile r:
+// up to 32 rows, half a column tile starting at r.n0) that meets one column group of that
+// slot's weights per wave.
 template <bool GATEUP, int NXF, int NGT, bool W8, bool RIDER, bool ONCE>
 __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, const Tile &r, unsigned char *smem,
                                                int K, int N, int ngroups, int nk4, int32_t lo_pos, int32_t *counter,
@@ -306,32 +379,33 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     constexpr int GC = GATEUP ? 16 : 32;
     constexpr int NXA = NXF + (RIDER ? 1 : 0);
     constexpr int PW = ring_depth(NXA);
+    constexpr int RING_R = rider_ring(NXF, W8);
     // The lane's constants (LDS offsets and the like) are derived afresh in every tile: hoisted
     // out of the tile loop they would stay live through the tallest tile, which has no
     // register to spare, and come back from scratch inside every contraction loop.
     const int lane = lane_index(), wave = wave_id;
     const int tid = wave * 64 + lane;
     const int lr = tid >> 3, kc = tid & 7;
-    const int frag_off = (lane & 31) * XROWB + (lane >> 5) * 16;
-    const int ksteps = nk4 * 16;
+    const int frag_off = (lane & 15) * XROWB + (lane >> 4) * 16;
+    const int ksteps = nk4 * 8;                    // 32-wide steps
     const int group0 = t.n0 / GC + wave * NGT;     // this wave's first column group
     const int group_r = r.n0 / GC + wave;          // and its one group of the rider
     const void *wbase = GATEUP ? a.wp_gateup[t.slot] : a.wp_down[t.slot];
     const void *wbase_r = RIDER ? (GATEUP ? a.wp_gateup[r.slot] : a.wp_down[r.slot]) : wbase;
-    // step-major stream: the fragments of all column groups for one step are adjacent.
-    // The packed buffer holds a multiple of kPackGroups groups (zero padded), so every wave
-    // of a tile has a stream to read even past the last real column.
+    // step-major stream: the fragments of all column groups for one step are adjacent, two per
+    // group.  The packed buffer holds a multiple of kPackGroups groups (zero padded), so every
+    // wave of a tile has a stream to read even past the last real column.
     const int groups_padded = (ngroups + kPackGroups - 1) / kPackGroups * kPackGroups;
     typedef typename WFrag<W8>::type F;
     Streams sm;
     sm.wb = uniform_base(wbase);
     sm.wbr = uniform_base(wbase_r);
-    sm.wl = (uint32_t)(group0 * 64 + lane) * (uint32_t)sizeof(F);
-    sm.wlr = (uint32_t)(group_r * 64 + lane) * (uint32_t)sizeof(F);
-    sm.wstep = (uint32_t)groups_padded * 64u * (uint32_t)sizeof(F);
+    sm.wl = (uint32_t)(group0 * 128 + lane) * (uint32_t)sizeof(F);
+    sm.wlr = (uint32_t)(group_r * 128 + lane) * (uint32_t)sizeof(F);
+    sm.wstep = (uint32_t)groups_padded * 128u * (uint32_t)sizeof(F);
     sm.wlast = (uint32_t)(ksteps - 1) * sm.wstep;  // the host checks that a packed matrix stays below 4 GiB
-    sm.woff = (uint32_t)(PW - 1) * sm.wstep;       // the loop's first refill is step PW (ksteps >= 16 >= PW)
-    sm.wroff = (uint32_t)(rider_ring(NXF, W8) - 1) * sm.wstep;
+    sm.woff = (uint32_t)(PW - 1) * sm.wstep;       // the loop's first refill is step PW (ksteps >= 8 >= PW)
+    sm.wroff = (uint32_t)(RING_R - 1) * sm.wstep;
     // Activation rows as 32-bit byte offsets from a uniform base.  Gate/up gathers token rows
     // from all over x (the host checks that x stays below 4 GiB); the down GEMM's rows follow
     // one another from the tile's first row on, the rider's from the rider's first row.
@@ -353,31 +427,37 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
         xp[i] = (uint32_t)(GATEUP ? a.src[pos] / a.k : rr) * row_bytes;
     }
 
-    f32x16_t acc[NGT][NXF], accr[1][1];
+    f32x4_t acc[NGT][2][2 * NXF], accr[1][2][2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) accr[0][0][v] = 0.0f;
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) accr[0][h][i] = (f32x4_t)(0.0f);
 #pragma unroll
     for (int n = 0; n < NGT; ++n)
 #pragma unroll
-        for (int g = 0; g < NXF; ++g)
+        for (int h = 0; h < 2; ++h)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[n][g][v] = 0.0f;
+            for (int g = 0; g < 2 * NXF; ++g) acc[n][h][g] = (f32x4_t)(0.0f);
 
     // Request order: half the weight rings, the first two activation slabs, the other half of
     // the rings.  The second slab is then followed by as many weight requests as in the loop,
     // so the in-order load counter need not be drained when the loop is entered.
-    typename WFrag<W8>::type wq[NGT][PW], wr[RIDER ? rider_ring(NXF, W8) : 1];
+    F wq[NGT][PW][2], wr[RIDER ? RING_R : 1][2];
     u32x4_t xr[NXA];
     {
         u32x4_t xfirst[NXA];
 #pragma unroll
         for (int j = 0; j < PW / 2; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + n * 64 * (int)sizeof(F), sm.wl);
+            for (int n = 0; n < NGT; ++n)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) wq[n][j][h] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + (2 * n + h) * 64 * (int)sizeof(F), sm.wl);
         if (RIDER)
 #pragma unroll
-            for (int j = 0; j < rider_ring(NXF, W8) / 2; ++j) wr[j] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep, sm.wlr);
-        if (!RIDER) wr[0] = zero_fragment<W8>();    // a placeholder that no MFMA reads
+            for (int j = 0; j < RING_R / 2; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) wr[j][h] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep + h * 64 * (int)sizeof(F), sm.wlr);
+        if (!RIDER) wr[0][0] = wr[0][1] = zero_fragment<W8>();    // placeholders that no MFMA reads
         const uint32_t k0 = (uint32_t)min(kc * 16, K * 2 - 16), k1 = (uint32_t)min(128 + kc * 16, K * 2 - 16);
 #pragma unroll
         for (int i = 0; i < NXA; ++i) xfirst[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + k0);
@@ -387,10 +467,14 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 #pragma unroll
         for (int j = PW / 2; j < PW; ++j)
 #pragma unroll
-            for (int n = 0; n < NGT; ++n) wq[n][j] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + n * 64 * (int)sizeof(F), sm.wl);
+            for (int n = 0; n < NGT; ++n)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) wq[n][j][h] = wload<ONCE, F>(sm.wb + (uint32_t)j * sm.wstep + (2 * n + h) * 64 * (int)sizeof(F), sm.wl);
         if (RIDER)
 #pragma unroll
-            for (int j = rider_ring(NXF, W8) / 2; j < rider_ring(NXF, W8); ++j) wr[j] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep, sm.wlr);
+            for (int j = RING_R / 2; j < RING_R; ++j)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) wr[j][h] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep + h * 64 * (int)sizeof(F), sm.wlr);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NXA; ++i)
@@ -398,9 +482,11 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     }
     __syncthreads();
 
+    // the lower fragments of the first step (the rider's 32 rows sit behind the tile's own)
     bf16x8_t x0[NXA], x1[NXA];
 #pragma unroll
-    for (int g = 0; g < NXA; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 32 * XROWB);
+    for (int g = 0; g < NXF; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 16 * XROWB);
+    if (RIDER) x0[NXA - 1] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + 32 * NXF * XROWB);
 
     const int last_slab = nk4 * 4 - 1;
     // the three LDS stages, s0 the one of the current slab: four slabs on, the roles have moved by one
@@ -422,11 +508,12 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     // wave-wide reduction whose result it waits for on the spot)
     int32_t claimed = 0;
     if (tid == 0) claimed = (int32_t)atomicInc(reinterpret_cast<unsigned int *>(counter), 0xffffffffu);
-    const size_t scale_off = (size_t)groups_padded * ksteps * 512;   // E4M3: row scales behind the codes
+    settle_accumulators<NGT, NXF>(acc, accr, RIDER);
+    const size_t scale_off = (size_t)groups_padded * ksteps * 1024;   // E4M3: row scales behind the codes
     store_fragments<GATEUP, NGT, NXF, W8>(
         a, t, acc, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase) + scale_off),
         group0, N, lo_pos);
-    if (RIDER)
+    if (RIDER)   // the rider's accumulators are those of a one-fragment, one-group tile
         store_fragments<GATEUP, 1, 1, W8>(
             a, r, accr, reinterpret_cast<const float *>(static_cast<const unsigned char *>(wbase_r) + scale_off),
             group_r, N, lo_pos);
@@ -551,27 +638,28 @@ __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
     }
 }
 
-// One 16-byte chunk of the packed stream per thread.
-//   gate/up : group g = output columns 16g..16g+15; fragment row r < 16 is gate row 16g+r,
-//             r >= 16 is up row 16g+r-16
-//   down    : group g = output columns 32g..32g+31; fragment row r is down row 32g+r
-// Lane l of step s holds fragment row (l & 31), contraction elements 16s + 8(l>>5) .. +7.
-// Rows and contraction elements past the matrix are zero.
+// One 16-byte chunk of the packed stream per thread: chunk ((step * groups + group) * 2 + half) * 64 + lane.
+//   gate/up : group g = output columns 16g..16g+15; half 0 = gate rows 16g..16g+15, half 1 = the
+//             up rows of the same columns
+//   down    : group g = output columns 32g..32g+31; half h = down rows 32g+16h..+15
+// Lane l of 32-wide step s holds row (l & 15) of its half, contraction elements 32s + 8(l>>4) .. +7:
+// the row operand of one v_mfma_f32_16x16x32_bf16.  Rows and contraction elements past the matrix are zero.
 __global__ void pack_kernel(const unsigned short *wa, const unsigned short *wb, int rows, int K,
                             int gc, int64_t nchunks, int ksteps, uint4 *out) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= nchunks) return;
     const int l = (int)(c & 63);
-    const int64_t sg = c >> 6;                   // step-major: chunk = (step * ngroups + group) * 64 + lane
-    const int64_t ngroups = nchunks / 64 / ksteps;   // padded to whole tiles of 8 groups
+    const int h = (int)(c >> 6) & 1;
+    const int64_t sg = c >> 7;                   // step-major
+    const int64_t ngroups = nchunks / 128 / ksteps;   // padded to whole tiles of 8 groups
     const int s = (int)(sg / ngroups);
     const int64_t g = sg % ngroups;
-    const int r = l & 31;
-    const int k0 = 16 * s + 8 * (l >> 5);
+    const int r = l & 15;
+    const int k0 = 32 * s + 8 * (l >> 4);
     int64_t row;
     const unsigned short *src;
-    if (gc == 16) { row = g * 16 + (r & 15); src = r < 16 ? wa : wb; }
-    else { row = g * 32 + r; src = wa; }
+    if (gc == 16) { row = g * 16 + r; src = h ? wb : wa; }
+    else { row = g * 32 + 16 * h + r; src = wa; }
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < rows && k0 < K) v = *reinterpret_cast<const uint4 *>(src + row * K + k0);
     out[c] = v;
@@ -610,10 +698,10 @@ hipError_t launch_pack(int32_t H, int32_t I, const void *wg, const void *wu, con
     const int64_t c1 = (int64_t)(gub / 16), c2 = (int64_t)(dnb / 16);
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((c1 + 255) / 256)), dim3(256), 0, s,
                        static_cast<const unsigned short *>(wg), static_cast<const unsigned short *>(wu),
-                       I, H, 16, c1, (H + 255) / 256 * 16, static_cast<uint4 *>(pgu));
+                       I, H, 16, c1, (H + 255) / 256 * 8, static_cast<uint4 *>(pgu));
     hipLaunchKernelGGL(pack_kernel, dim3((unsigned)((c2 + 255) / 256)), dim3(256), 0, s,
                        static_cast<const unsigned short *>(wd), static_cast<const unsigned short *>(wd),
-                       H, I, 32, c2, (I + 255) / 256 * 16, static_cast<uint4 *>(pdn));
+                       H, I, 32, c2, (I + 255) / 256 * 8, static_cast<uint4 *>(pdn));
     return hipGetLastError();
 }
 

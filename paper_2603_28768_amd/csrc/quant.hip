@@ -49,26 +49,28 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_e4m3_kernel(const unsi
 }
 
 // One 8-byte chunk of the packed stream per thread: the layout of the bf16 stream (step-major,
-// 8 column groups per tile, 64 lanes per fragment), with 8 codes where it has 8 bf16 values.
-//   gate/up : group g = output columns 16g..16g+15; fragment row r < 16 is gate row 16g+r,
-//             r >= 16 is up row 16g+r-16
-//   down    : group g = output columns 32g..32g+31; fragment row r is down row 32g+r
-// Lane l of step s holds fragment row (l & 31), contraction elements 16s + 8(l>>5) .. +7.
+// 8 column groups per tile, two 16-row fragments per group, 64 lanes per fragment), with 8 codes
+// where it has 8 bf16 values.
+//   gate/up : group g = output columns 16g..16g+15; half 0 = gate rows 16g..16g+15, half 1 = the
+//             up rows of the same columns
+//   down    : group g = output columns 32g..32g+31; half h = down rows 32g+16h..+15
+// Lane l of 32-wide step s holds row (l & 15) of its half, contraction elements 32s + 8(l>>4) .. +7.
 __global__ void pack_e4m3_kernel(const uint8_t *ca, const uint8_t *cb, int rows, int K, int gc,
                                  int64_t nchunks, int ksteps, uint2 *out) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= nchunks) return;
     const int l = (int)(c & 63);
-    const int64_t sg = c >> 6;
-    const int64_t ngroups = nchunks / 64 / ksteps;
+    const int h = (int)(c >> 6) & 1;
+    const int64_t sg = c >> 7;
+    const int64_t ngroups = nchunks / 128 / ksteps;
     const int s = (int)(sg / ngroups);
     const int64_t g = sg % ngroups;
-    const int r = l & 31;
-    const int k0 = 16 * s + 8 * (l >> 5);
+    const int r = l & 15;
+    const int k0 = 32 * s + 8 * (l >> 4);
     int64_t row;
     const uint8_t *src;
-    if (gc == 16) { row = g * 16 + (r & 15); src = r < 16 ? ca : cb; }
-    else { row = g * 32 + r; src = ca; }
+    if (gc == 16) { row = g * 16 + r; src = h ? cb : ca; }
+    else { row = g * 32 + 16 * h + r; src = ca; }
     uint2 v = make_uint2(0, 0);
     if (row < rows && k0 < K) v = *reinterpret_cast<const uint2 *>(src + row * K + k0);
     out[c] = v;
@@ -104,9 +106,9 @@ hipError_t launch_pack_e4m3(int32_t H, int32_t I, const uint8_t *cg, const uint8
     const size_t gu_stream = gub - (size_t)2 * I * sizeof(float), dn_stream = dnb - (size_t)H * sizeof(float);
     const int64_t c1 = (int64_t)(gu_stream / 8), c2 = (int64_t)(dn_stream / 8);
     hipLaunchKernelGGL(pack_e4m3_kernel, dim3((unsigned)((c1 + 255) / 256)), dim3(256), 0, s, cg, cu, I, H,
-                       16, c1, (H + 255) / 256 * 16, static_cast<uint2 *>(pgu));
+                       16, c1, (H + 255) / 256 * 8, static_cast<uint2 *>(pgu));
     hipLaunchKernelGGL(pack_e4m3_kernel, dim3((unsigned)((c2 + 255) / 256)), dim3(256), 0, s, cd, cd, H, I,
-                       32, c2, (I + 255) / 256 * 16, static_cast<uint2 *>(pdn));
+                       32, c2, (I + 255) / 256 * 8, static_cast<uint2 *>(pdn));
     float *gus = reinterpret_cast<float *>(static_cast<unsigned char *>(pgu) + gu_stream);
     float *dns = reinterpret_cast<float *>(static_cast<unsigned char *>(pdn) + dn_stream);
     hipLaunchKernelGGL(copy_scales_kernel, dim3((unsigned)((2 * I + 255) / 256)), dim3(256), 0, s, sg, su, I, gus);

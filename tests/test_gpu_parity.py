@@ -467,20 +467,22 @@ def test_packed_weights_layout(torch_cuda):
     Wg, Wu, Wd = mats
 
     def expect(groups, ksteps, row_of, K):
-        out = np.zeros((ksteps, groups, 64, 8), np.float32)
+        # [32-wide step][column group][half][lane][8 values]
+        out = np.zeros((ksteps, groups, 2, 64, 8), np.float32)
         for gi in range(groups):
             for s in range(ksteps):
-                for l in range(64):
-                    src = row_of(gi, l & 31)
-                    k0 = 16 * s + 8 * (l >> 5)
-                    if src is not None and k0 < K:
-                        out[s, gi, l] = src[k0:k0 + 8]
+                for h in range(2):
+                    for l in range(64):
+                        src = row_of(gi, h, l & 15)
+                        k0 = 32 * s + 8 * (l >> 4)
+                        if src is not None and k0 < K:
+                            out[s, gi, h, l] = src[k0:k0 + 8]
         return out.reshape(-1)
 
-    gu = expect(((I + 15) // 16 + 7) // 8 * 8, (H + 255) // 256 * 16,
-                lambda gi, r: (Wg if r < 16 else Wu)[16 * gi + (r & 15)] if 16 * gi + (r & 15) < I else None, H)
-    dn = expect(((H + 31) // 32 + 7) // 8 * 8, (I + 255) // 256 * 16,
-                lambda gi, r: Wd[32 * gi + r] if 32 * gi + r < H else None, I)
+    gu = expect(((I + 15) // 16 + 7) // 8 * 8, (H + 255) // 256 * 8,
+                lambda gi, h, r: (Wu if h else Wg)[16 * gi + r] if 16 * gi + r < I else None, H)
+    dn = expect(((H + 31) // 32 + 7) // 8 * 8, (I + 255) // 256 * 8,
+                lambda gi, h, r: Wd[32 * gi + 16 * h + r] if 32 * gi + 16 * h + r < H else None, I)
     assert np.array_equal(pgu, gu) and np.array_equal(pdn, dn)
 
 
