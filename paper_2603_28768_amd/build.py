@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -27,9 +28,56 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# Sources whose matrix instructions are written as asm statements, which the compiler's hazard
+# pass does not recognise: their emitted code is checked here instead (check_matrix_operands).
+ASM_MFMA_SOURCES = {"ffn_packed.hip"}
+
+
+def _registers(token: str) -> set:
+    token = token.strip().rstrip(",")
+    m = re.match(r"^([va])\[(\d+):(\d+)\]$", token)
+    if m:
+        return {(m.group(1), r) for r in range(int(m.group(2)), int(m.group(3)) + 1)}
+    m = re.match(r"^([va])(\d+)$", token)
+    return {(m.group(1), int(m.group(2)))} if m else set()
+
+
+def check_matrix_operands(asm_path: str) -> int:
+    """A matrix instruction may read a register that an ordinary vector instruction wrote two
+    issue cycles later at the earliest.  For the matrix instructions the compiler emits itself
+    it inserts the wait; here every v_mfma of the emitted gfx950 code is checked against the two
+    instructions in front of it (an s_nop of two or more cycles in between settles it).  Returns
+    the number of matrix instructions checked; raises on a violation."""
+    ins = [l.strip() for l in open(asm_path) if l.startswith("\t") and not l.lstrip().startswith((";", "."))]
+    checked, bad = 0, []
+    for k, t in enumerate(ins):
+        if not t.startswith("v_mfma"):
+            continue
+        checked += 1
+        ops = t.split(None, 1)[1].split(";")[0].split(",")
+        src = set().union(*[_registers(o) for o in ops[1:]])
+        for back in (1, 2):
+            if k - back < 0:
+                break
+            p = ins[k - back]
+            if p.startswith("s_nop"):
+                if int(p.split()[1]) + 1 >= 2:
+                    break
+                continue
+            if p.startswith("v_") and not p.startswith("v_mfma"):
+                if _registers(p.split(None, 1)[1].split(",")[0]) & src:
+                    bad.append(f"{p}  ->  {t}")
+    if bad:
+        raise RuntimeError(f"{asm_path}: {len(bad)} matrix instructions read a register written by one of the two "
+                           "vector instructions in front of them, e.g.\n  " + "\n  ".join(bad[:5]))
+    return checked
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src + ".o")
     cmd = [_hipcc(), *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    if src in ASM_MFMA_SOURCES:
+        cmd.insert(-2, "-save-temps=obj")
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -37,6 +85,14 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    if src in ASM_MFMA_SOURCES:
+        stem = os.path.join(OBJ, src.rsplit(".", 1)[0])
+        n = check_matrix_operands(stem + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        if n == 0:
+            raise RuntimeError(f"{src}: no matrix instruction found in the emitted code")
+        for f in os.listdir(OBJ):                  # the intermediate files are not kept
+            if f.startswith(os.path.basename(stem) + "-") or f.startswith(src + "-"):
+                os.remove(os.path.join(OBJ, f))
     return obj
 
 
