@@ -340,7 +340,7 @@ def machine_rates(steps=10):
     sink = torch.empty(8 * 1024 * 256, dtype=torch.float32, device="cuda")
     isink = torch.empty(8 * 1024 * 256, dtype=torch.int32, device="cuda")
     small = torch.ones(2 << 20, dtype=torch.uint8, device="cuda")     # fits every XCD's L2
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(6)]
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(10)]
     for _ in range(3):
         binding.probe_copy(a, b)
         binding.probe_mfma_bf16(2000, sink)
@@ -360,10 +360,21 @@ def machine_rates(steps=10):
     for _ in range(steps):
         flops += binding.probe_mfma_bf16(20000, sink)
     ev[3].record()
+    # the same matrix work on operands with random signs and mantissas, in the shape the FFN
+    # uses (16x16x32) and in the other one: what the power the matrix pipelines draw leaves
+    rnd = []
+    for n_ev, shape in ((6, 1), (8, 0)):
+        binding.probe_mfma_operands(shape, 2, 2000, sink)
+        ev[n_ev].record()
+        fl = sum(binding.probe_mfma_operands(shape, 2, 30000, sink) for _ in range(2))
+        ev[n_ev + 1].record()
+        rnd.append(fl)
     torch.cuda.synchronize()
     assert bool((b == 1).all())
     return dict(copy_gbs=2.0 * n * steps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
                 mfma_bf16_tflops=flops / (ev[2].elapsed_time(ev[3]) * 1e-3) / 1e12,
+                mfma_bf16_random_operands_16x16x32_tflops=rnd[0] / (ev[6].elapsed_time(ev[7]) * 1e-3) / 1e12,
+                mfma_bf16_random_operands_32x32x16_tflops=rnd[1] / (ev[8].elapsed_time(ev[9]) * 1e-3) / 1e12,
                 l2_read_gbs=l2_bytes / (ev[4].elapsed_time(ev[5]) * 1e-3) / 1e9)
 
 
@@ -589,11 +600,17 @@ def main():
                                 frac_of_no_overlap=no_ov / ffn_ms if ffn_ms else None,
                                 frac_of_perfect_overlap=perfect / ffn_ms if ffn_ms else None),
                 machine=dict(copy_gbs=rates["copy_gbs"], mfma_bf16_tflops=rates["mfma_bf16_tflops"],
+                             mfma_bf16_random_operands_16x16x32_tflops=rates["mfma_bf16_random_operands_16x16x32_tflops"],
+                             mfma_bf16_random_operands_32x32x16_tflops=rates["mfma_bf16_random_operands_32x32x16_tflops"],
                              l2_read_gbs=rates["l2_read_gbs"],
                              frac_of_measured_copy=gbs / rates["copy_gbs"],
                              frac_of_measured_mfma=tfs / rates["mfma_bf16_tflops"],
+                             frac_of_measured_mfma_random_operands=tfs / rates["mfma_bf16_random_operands_16x16x32_tflops"],
                              what="craft_probe_copy of 256 MiB (bytes read + written per second), "
-                                  "craft_probe_mfma_bf16 (register-only v_mfma_f32_32x32x16_bf16 loop) and "
+                                  "craft_probe_mfma_bf16 (register-only v_mfma_f32_32x32x16_bf16 loop on small integers), "
+                                  "craft_probe_mfma_operands (register-only loops of either MFMA shape on operands with "
+                                  "random signs and mantissas: the rate the chip's power limit leaves on data like the "
+                                  "FFN's; the FFN uses 16x16x32) and "
                                   "craft_probe_read (every workgroup re-reading a 2 MiB buffer out of L2) on this GPU"))
 
     if len(states) == 1:

@@ -405,7 +405,7 @@ craft_status craft_timing_enable(int32_t level, int32_t max_forwards);
 craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_K_COUNT]);
 
 /* ------------------------------------------------------------ measurement probes
- * Not part of the method: two kernels of known work, so that a benchmark can report this
+ * Not part of the method: kernels of known work, so that a benchmark can report this
  * machine's own ceilings next to the published ones and scale memory counters.
  * craft_probe_copy: dst[i] = src[i] for `bytes` bytes (a multiple of 16; both DEVICE, 16-byte
  *   aligned, not overlapping): reads `bytes` and writes `bytes`, nothing else.
@@ -419,12 +419,24 @@ craft_status craft_timing_read(double ms[CRAFT_K_COUNT], int64_t launches[CRAFT_
  *   requests in total.  With a buffer of a megabyte or two, which the L2 of every XCD holds
  *   and the L1 of a compute unit does not, this measures what all compute units together
  *   can pull out of L2.
+ * craft_probe_mfma_operands: the matrix rate as a function of the operands' contents and of
+ *   the instruction's shape (the clock the chip sustains depends on both).  blocks x 4
+ *   wavefronts (blocks = 0: one workgroup per compute unit), each with the register shape of
+ *   an FFN tile (2 x 8 operand fragments per step, 256 accumulator registers), issue per
+ *   iteration the work of 32 products of 32 x 32 x 16 as
+ *     shape 0: v_mfma_f32_32x32x16_bf16    shape 1: v_mfma_f32_16x16x32_bf16
+ *   on operands holding
+ *     data 0: zeros    1: the values 1.0 and 1.5    2: random signs and mantissas, exponents
+ *     spread over eight binades below 1
+ *   sink DEVICE [blocks * 256] float; *flops as for craft_probe_mfma_bf16.
  * All only enqueue on `stream`; time them with events on that stream. */
 craft_status craft_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
 craft_status craft_probe_read(const void *src, int64_t bytes, int32_t passes, int32_t blocks,
                               uint32_t *sink, double *bytes_read, void *stream);
 craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, double *flops,
                                    void *stream);
+craft_status craft_probe_mfma_operands(int32_t shape, int32_t data, int32_t blocks, int32_t iters,
+                                       float *sink, double *flops, void *stream);
 
 #ifdef __cplusplus
 }

@@ -78,6 +78,7 @@ EXPORTS = {
     "craft_probe_copy": (ctypes.c_int, [c_vp, c_vp, c_i64, c_vp]),
     "craft_probe_read": (ctypes.c_int, [c_vp, c_i64, c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
     "craft_probe_mfma_bf16": (ctypes.c_int, [c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
+    "craft_probe_mfma_operands": (ctypes.c_int, [c_i32, c_i32, c_i32, c_i32, c_vp, P(ctypes.c_double), c_vp]),
     "craft_timing_enable": (ctypes.c_int, [c_i32, c_i32]),
     "craft_timing_read": (ctypes.c_int, [P(ctypes.c_double), P(c_i64)]),
 }
@@ -476,6 +477,16 @@ def probe_mfma_bf16(iters: int, sink, blocks: int = 0, stream=None) -> float:
     fl = ctypes.c_double()
     _check(lib().craft_probe_mfma_bf16(blocks, iters, _dev(sink), fl, _stream_ptr(stream)),
            "craft_probe_mfma_bf16")
+    return fl.value
+
+
+def probe_mfma_operands(shape: int, data: int, iters: int, sink, blocks: int = 0, stream=None) -> float:
+    """Enqueue the matrix loop of the given instruction shape (0: 32x32x16, 1: 16x16x32) on operands
+    of the given contents (0 zeros, 1 small values, 2 random); returns its floating-point operations.
+    sink: device float32 tensor with at least blocks * 256 elements (blocks = 0: 1 per CU)."""
+    fl = ctypes.c_double()
+    _check(lib().craft_probe_mfma_operands(shape, data, blocks, iters, _dev(sink), fl, _stream_ptr(stream)),
+           "craft_probe_mfma_operands")
     return fl.value
 
 

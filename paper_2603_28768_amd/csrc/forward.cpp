@@ -654,6 +654,17 @@ craft_status craft_probe_mfma_bf16(int32_t blocks, int32_t iters, float *sink, d
     return launch_probe_mfma(blocks, iters, sink, as_stream(stream)) == hipSuccess ? CRAFT_OK : CRAFT_EHIP;
 }
 
+craft_status craft_probe_mfma_operands(int32_t shape, int32_t data, int32_t blocks, int32_t iters, float *sink,
+                                       double *flops, void *stream) {
+    if (shape < 0 || shape > 1 || data < 0 || data > 2) return CRAFT_EINVAL;
+    if (blocks < 0 || blocks > (1 << 20) || iters <= 0 || !sink || !aligned(sink, 4)) return CRAFT_EINVAL;
+    if (blocks == 0) blocks = cached_num_cu();
+    // per wave and iteration: two steps of 2 x 8 products of 32 x 32 x 16
+    if (flops) *flops = (double)blocks * 4.0 * (double)iters * 32.0 * 2.0 * 32.0 * 32.0 * 16.0;
+    return launch_probe_mfma_operands(shape, data, blocks, iters, sink, as_stream(stream)) == hipSuccess ? CRAFT_OK
+                                                                                                        : CRAFT_EHIP;
+}
+
 craft_status craft_timing_enable(int32_t level, int32_t max_forwards) {
     if (level < 0 || level > 2 || max_forwards < 0) return CRAFT_EINVAL;
     Timing &t = g_timing;

@@ -174,6 +174,8 @@ hipError_t launch_probe_copy(const void *src, void *dst, int64_t bytes, int32_t 
 hipError_t launch_probe_read(const void *src, int64_t bytes, int32_t passes, int32_t blocks, uint32_t *sink,
                              hipStream_t s);
 hipError_t launch_probe_mfma(int32_t blocks, int32_t iters, float *sink, hipStream_t s);
+hipError_t launch_probe_mfma_operands(int32_t shape, int32_t data, int32_t blocks, int32_t iters, float *sink,
+                                      hipStream_t s);
 hipError_t launch_load_accumulate(const int32_t *counts, int64_t n, int64_t *window, hipStream_t s);
 
 }  // namespace craft

@@ -66,7 +66,104 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink)
     sink[(int64_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// The matrix rate as a function of what the operands hold and of the instruction's shape.  The
+// chip lowers its clock under the power the matrix pipelines draw, and that power depends on
+// how many operand bits change from one instruction to the next: a loop over zeros or small
+// integers says little about a GEMM on real activations.  Every wave keeps the FFN tile's
+// register shape (2 weight x 8 activation fragments per step, 256 accumulator registers, two
+// steps of distinct operands taken in turn) and issues the same floating-point work per
+// iteration with either shape; nothing is loaded.
+//   data 0: zeros;  1: the values 1.0 and 1.5;  2: random signs and mantissas, exponents spread
+//   over 2^-8 .. 2^-1 (products and sums stay far from overflow for any iteration count)
+static __device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+static __device__ __forceinline__ bf16x8_t probe_operand(uint32_t seed, int data) {
+    u32x4_t r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t h = probe_hash(seed * 4 + i);
+        uint32_t lo = 0, hi = 0;
+        if (data == 1) { lo = 0x3f80 + ((h & 1) << 6); hi = 0x3f80 + ((h >> 1 & 1) << 6); }
+        if (data == 2) { lo = (h & 0x807f) | ((119 + (h >> 8 & 7)) << 7); hi = ((h >> 16) & 0x807f) | ((119 + (h >> 24 & 7)) << 7); }
+        r[i] = lo | (hi << 16);
+    }
+    return __builtin_bit_cast(bf16x8_t, r);
+}
+template <int SHAPE>   // 0: v_mfma_f32_32x32x16_bf16, 1: v_mfma_f32_16x16x32_bf16
+__global__ __launch_bounds__(256, 1) void probe_mfma_operands_kernel(int iters, int data, float *sink) {
+    bf16x8_t w[2][2], x[2][8];
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+#pragma unroll
+        for (int n = 0; n < 2; ++n) w[s][n] = probe_operand(t * 64 + s * 16 + n, data);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) x[s][g] = probe_operand(t * 64 + s * 16 + 2 + g, data);
+    }
+    float sum = 0.0f;
+    if (SHAPE == 0) {
+        f32x16_t acc[2][8];
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int g = 0; g < 8; ++g) acc[n][g] = (f32x16_t)(0.0f);
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int n = 0; n < 2; ++n)
+#pragma unroll
+                    for (int g = 0; g < 8; ++g)
+                        acc[n][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[s][n], x[s][g], acc[n][g], 0, 0, 0);
+        }
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += acc[n][g][v];
+    } else {
+        // a 32 x 32 block of outputs over 32 contraction elements: four products of 16 x 16 x 32
+        f32x4_t acc[2][8][4];
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[n][g][q] = (f32x4_t)(0.0f);
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int n = 0; n < 2; ++n)
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    acc[n][g][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[0][n], x[0][g], acc[n][g][0], 0, 0, 0);
+                    acc[n][g][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[0][n], x[1][g], acc[n][g][1], 0, 0, 0);
+                    acc[n][g][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[1][n], x[0][g], acc[n][g][2], 0, 0, 0);
+                    acc[n][g][3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[1][n], x[1][g], acc[n][g][3], 0, 0, 0);
+                }
+        }
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) sum += acc[n][g][q][v];
+    }
+    sink[t] = sum;
+}
+
 }  // namespace
+
+hipError_t launch_probe_mfma_operands(int32_t shape, int32_t data, int32_t blocks, int32_t iters, float *sink,
+                                      hipStream_t s) {
+    if (shape == 0) hipLaunchKernelGGL(probe_mfma_operands_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, s, iters, data, sink);
+    else hipLaunchKernelGGL(probe_mfma_operands_kernel<1>, dim3((unsigned)blocks), dim3(256), 0, s, iters, data, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_probe_copy(const void *src, void *dst, int64_t bytes, int32_t num_cu, hipStream_t s) {
     const int64_t n = bytes / 16;
