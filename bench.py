@@ -291,12 +291,12 @@ def copy_calibration(args):
 # (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
 # is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-_SHA = "5229c3f26574bd03f1fec1923f108f5662677bec5fbb3a9cc04ef6b8149a6252"
+_SHA = "7fa197998cc2d9de08fa89ff0cf2deb49dc90a291cadca89ce37693567f45930"
 TRAFFIC = {
-    "qwen3": dict(fetch_kib=290426.4, write_kib=15273.3, fetch_scale=2.0, write_scale=1.0, mfma_util=0.407, mfma_busy_of_peak_clock=0.354, l2_to_cu_mb=1284.1, l2_hit=0.549, sources_sha256=_SHA),
-    "dsv3": dict(fetch_kib=198063.7, write_kib=11777.2, fetch_scale=2.0, write_scale=1.0, mfma_util=0.523, mfma_busy_of_peak_clock=0.429, l2_to_cu_mb=1534.9, l2_hit=0.736, sources_sha256=_SHA),
-    "kimi": dict(fetch_kib=175978.4, write_kib=12171.6, fetch_scale=2.0, write_scale=1.0, mfma_util=0.506, mfma_busy_of_peak_clock=0.416, l2_to_cu_mb=1398.7, l2_hit=0.744, sources_sha256=_SHA),
-    "stack": dict(fetch_kib=972059.0, write_kib=86118.2, fetch_scale=2.0, write_scale=1.0, mfma_util=0.708, mfma_busy_of_peak_clock=0.507, l2_to_cu_mb=8847.0, l2_hit=0.771, sources_sha256=_SHA),
+    "qwen3": dict(fetch_kib=284626.4, write_kib=12742.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.403, mfma_busy_of_peak_clock=0.367, l2_to_cu_mb=1289.5, l2_hit=0.551, sources_sha256=_SHA),
+    "dsv3": dict(fetch_kib=197890.8, write_kib=9473.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.49, mfma_busy_of_peak_clock=0.431, l2_to_cu_mb=1537.9, l2_hit=0.735, sources_sha256=_SHA),
+    "kimi": dict(fetch_kib=177793.0, write_kib=10155.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.516, mfma_busy_of_peak_clock=0.448, l2_to_cu_mb=1404.2, l2_hit=0.739, sources_sha256=_SHA),
+    "stack": dict(fetch_kib=1004548.7, write_kib=75048.1, fetch_scale=2.0, write_scale=1.0, mfma_util=0.691, mfma_busy_of_peak_clock=0.538, l2_to_cu_mb=8886.6, l2_hit=0.761, sources_sha256=_SHA),
 }
 
 

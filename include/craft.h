@@ -282,7 +282,9 @@ craft_status craft_pack_weights_e4m3(int32_t H, int32_t I, const uint8_t *gate_c
  *   w_gateup_packed, w_down_packed  DEVICE arrays of s device pointers to the buffers
  *                 craft_pack_weights filled for each slot's expert.  When both are given
  *                 (bf16 only) the FFN streams these and w_gate / w_up / w_down may be NULL;
- *                 when NULL the FFN reads the row-major matrices.
+ *                 when NULL the FFN reads the row-major matrices.  The streaming kernels
+ *                 address token rows and weight fragments by 32-bit byte offsets: x (T * H
+ *                 elements) and each packed matrix must stay below 4 GiB, else CRAFT_EINVAL.
  *   weight_format of the packed buffers: CRAFT_W_BF16 (craft_pack_weights) or CRAFT_W_E4M3
  *                 (craft_pack_weights_e4m3)
  *   out      DEVICE [T][H] dtype, fully overwritten
