@@ -52,14 +52,23 @@ namespace {
 // 32-wide weight steps kept in flight per column group: deep for the streaming-bound tiles with
 // few row fragments, shallower where the accumulators need the registers and each step carries
 // enough MFMA work to cover the latency.
-constexpr int ring_depth(int nxa) { return nxa >= 3 ? 4 : 8; }
+#ifndef RING_TALL
+#define RING_TALL 8
+#endif
+constexpr int ring_depth(int nxa) { return nxa >= 3 ? RING_TALL : 8; }
 // The rider's weights always come from HBM (nobody else reads them): where the registers are
 // there its ring runs twice as far ahead as the tile's own.
 constexpr int rider_ring(int nxf, bool w8) { return w8 || nxf <= 4 ? 8 : 4; }
 constexpr int NG = 2;             // column groups per wave in a full-width tile (1 in a half-width one)
 constexpr int kPackGroups = 8;    // the packed stream is padded to whole full-width tiles
-constexpr int XROWB = 64 * 2 + 16;
+// An LDS stage holds one 64-wide slab of up to 256 activation rows, 128 bytes per row, no
+// padding: the rows arrive by loads that write LDS directly, 64 lanes x 16 bytes to consecutive
+// addresses.  So that the fragment reads (16 rows at one contraction offset) still spread over
+// all banks (eight lanes, eight consecutive rows, are served per cycle), the eight 16-byte pieces
+// of row r are stored in the order piece ^ (r & 7).
+constexpr int XROWB = 64 * 2;
 constexpr int XSTAGEB = kBM_packed * XROWB;
+constexpr int kStages = 4;
 
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 // A weight fragment as it sits in the ring: 8 bf16 values, or 8 E4M3 codes that are widened
@@ -95,8 +104,23 @@ static __device__ __forceinline__ ubase_t uniform_base(const void *p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return reinterpret_cast<ubase_t>(((uint64_t)hi << 32) | lo);
 }
-static __device__ __forceinline__ u32x4_t xload(ubase_t base, uint32_t off) {
-    return *(const u32x4_t __attribute__((address_space(1))) *)(base + off);
+// 16 bytes per lane from base + off straight into LDS at lds + 16 * lane (lds: the byte address
+// of the wave's 1 KiB destination, wave-uniform; it goes through M0, which the compiler keeps
+// nothing in across statements).  The compiler does not know that this is a load: it neither
+// counts it among the outstanding requests (its own waits for other loads then only wait longer
+// than needed, requests complete in order) nor waits for it before LDS reads (dma_wait does).
+static __device__ __forceinline__ void dma_chunk(ubase_t base, uint32_t off, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds), "v"(off), "s"(base) : "memory");
+}
+// the same in two statements, with at least one instruction between them
+static __device__ __forceinline__ void dma_to(uint32_t lds) { asm volatile("s_mov_b32 m0, %0" :: "s"(lds) : "memory"); }
+static __device__ __forceinline__ void dma_request(ubase_t base, uint32_t off) {
+    asm volatile("global_load_lds_dwordx4 %0, %1" :: "v"(off), "s"(base) : "memory");
+}
+// wait until at most N of this wave's requests are outstanding
+template <int N> static __device__ __forceinline__ void dma_wait() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 // The lane's index inside its wave, counted afresh from the execution mask: with the wave's
 // index kept in a scalar register no vector register has to carry the thread index through
@@ -176,29 +200,24 @@ static __device__ __forceinline__ void settle_accumulators(f32x4_t (&acc)[NGT][2
 // per MFMA, and a scheduling barrier after each MFMA pins that order.
 //   MFMA m < NXF           : + LDS read of fragment m of the FOLLOWING half-step into XN (this
 //                            one runs on XC; a whole half-step of matrix work covers the latency)
-//   the last MFMAs, STAGE  : the lower half-steps of a slab move the activation rows of the next
-//   0 / 1                    slab from XR to LDS stage `nxt` (first / second half of the row
-//                            chunks), a chunk's LDS write behind one MFMA, the request that
-//                            refills its registers for the slab after that behind the next
+//   the last MFMAs, STAGE  : a slab's first half-step requests the activation rows of the slab two
+//   0                        ahead, which land in LDS by themselves (dma_chunk), one 32-row chunk
+//                            behind each MFMA
 //   HI, a fragment's last  : + refill of the ring slot that weight fragment came from
 //   the rider, if any      : fragment NXF of the activations is 16 rows of a cold slot (its lower
 //                            16 in the lower half-step) and meets one column group of that
 //                            slot's weights (a ring of its own): two more MFMAs at the end
 template <int NXF, int NGT, int R, int RR, int PW, int HI, int STAGE, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_half(const unsigned char *xnext, Streams &sm,
+__device__ __forceinline__ void packed_half(uint32_t xnext, Streams &sm,
                                             typename WFrag<W8>::type (&wq)[NGT][PW][2],
                                             typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1][2],
                                             const bf16x8_t (&XC)[NXF + RIDER], bf16x8_t (&XN)[NXF + RIDER],
-                                            f32x4_t (&acc)[NGT][2][2 * NXF], f32x4_t (&accr)[1][2][2], unsigned char *xstage,
-                                            u32x4_t (&XR)[NXF + RIDER], const uint32_t (&xp)[NXF + RIDER],
-                                            uint32_t koff) {
+                                            f32x4_t (&acc)[NGT][2][2 * NXF], f32x4_t (&accr)[1][2][2], uint32_t dma_lds,
+                                            const uint32_t (&xp)[NXF + RIDER], uint32_t koff) {
     typedef typename WFrag<W8>::type F;
     constexpr int NXA = NXF + (RIDER ? 1 : 0);     // activation fragments of a half in LDS, the rider's last
-    constexpr int HALF = (NXA + 1) / 2;
     constexpr int M = 2 * NGT * NXF + (RIDER ? 2 : 0);                 // MFMAs of this half-step
-    constexpr int C0 = STAGE < 0 ? 0 : STAGE * HALF;                   // row chunks staged here: C0 .. C1 - 1
-    constexpr int C1 = STAGE < 0 ? 0 : (NXA < (STAGE + 1) * HALF ? NXA : (STAGE + 1) * HALF);
-    constexpr int OP0 = M - 2 * (C1 - C0) > 0 ? M - 2 * (C1 - C0) : 0; // MFMA behind which the first staging operation goes
+    constexpr int OP0 = M - 2 * NXA > 0 ? M - 2 * NXA : 0;             // MFMA behind which the first row chunk is prepared
     constexpr int NH = 1 - HI;                     // the half that is fetched from LDS meanwhile
     constexpr int RING_R = rider_ring(NXF, W8);
     if (HI) {
@@ -206,16 +225,24 @@ __device__ __forceinline__ void packed_half(const unsigned char *xnext, Streams 
         if (RIDER) sm.wroff = min(sm.wroff + sm.wstep, sm.wlast);
     }
     const ubase_t wcur = sm.wb + sm.woff, wrcur = sm.wbr + sm.wroff;
+    // xnext: the LDS address of the lane's piece of the first fragment to fetch.  Kept as one
+    // register per half-step with the fragments at constant offsets from it: folded together
+    // with the stage's offset the constants no longer fit the instruction and every read got an
+    // address computation of its own.
+    asm volatile("" : "+v"(xnext));
+    typedef const bf16x8_t __attribute__((address_space(3))) *lds_frag_t;
     // what follows MFMA m
     auto after = [&](int m) __attribute__((always_inline)) {
-        if (m < NXF) XN[m] = *reinterpret_cast<const bf16x8_t *>(xnext + 16 * (NH * NXF + m) * XROWB);
-        if (RIDER && m == NXF) XN[NXA - 1] = *reinterpret_cast<const bf16x8_t *>(xnext + (32 * NXF + 16 * NH) * XROWB);
+        if (m < NXF) XN[m] = *(lds_frag_t)(uintptr_t)(xnext + 16 * (NH * NXF + m) * XROWB);
+        if (RIDER && m == NXF) XN[NXA - 1] = *(lds_frag_t)(uintptr_t)(xnext + (32 * NXF + 16 * NH) * XROWB);
+        if (STAGE == 0) {
 #pragma unroll
-        for (int i = C0; i < C1; ++i) {
-            const int w_at = OP0 + 2 * (i - C0) < M - 1 ? OP0 + 2 * (i - C0) : M - 1;
-            const int r_at = OP0 + 2 * (i - C0) + 1 < M - 1 ? OP0 + 2 * (i - C0) + 1 : M - 1;
-            if (m == w_at) *reinterpret_cast<u32x4_t *>(xstage + 32 * i * XROWB) = XR[i];
-            if (m == r_at) XR[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + koff);
+            for (int i = 0; i < NXA; ++i) {
+                // destination behind one MFMA, request behind the next: together they would
+                // take longer to issue than an MFMA keeps the matrix pipeline busy
+                if (m == (OP0 + 2 * i < M - 1 ? OP0 + 2 * i : M - 1)) dma_to(dma_lds + 32 * i * XROWB);
+                if (m == (OP0 + 2 * i + 1 < M - 1 ? OP0 + 2 * i + 1 : M - 1)) dma_request(i < NXF ? sm.xb : sm.xbr, xp[i] + koff);
+            }
         }
     };
 #pragma unroll
@@ -244,32 +271,37 @@ __device__ __forceinline__ void packed_half(const unsigned char *xnext, Streams 
     }
 }
 
-// One 64-wide slab U (0..3) of a group of four: two 32-wide steps, four half-steps.  On entry
-// LDS stage `cur` holds this slab, XR the next slab (in registers, requested one slab ago) and
-// X0 the lower fragments of this slab's first step.  During the two lower half-steps XR goes
-// into stage `nxt` and the slab two ahead is requested from global memory into the same
-// registers; the last half-step already fetches the first fragments of the next slab.  Three
-// LDS stages make one barrier per slab enough: a stage is rewritten a full slab after its last
-// reader has passed a barrier.
+// One 64-wide slab U (0..3) of a group of four: two 32-wide steps, four half-steps.  The slab
+// sits in LDS stage U (four stages: a group of four slabs goes once round them); X0 holds the
+// lower fragments of its first step.  The first half-step requests the rows of slab U + 2 into
+// stage (U + 2) % 4; before the barrier in front of the last half-step, which already reads the
+// first fragments of slab U + 1, every wave waits for the requests it issued one slab ago (the
+// rows of slab U + 1): since then it has issued the weight refills of three steps and the row
+// requests of this slab, and requests complete in order.  A stage is overwritten two slabs after
+// it was last read, with the barrier of the slab in between.
 template <int NXF, int NGT, int U, int PW, bool W8, bool RIDER, bool ONCE>
-__device__ __forceinline__ void packed_slab(int ks, int last_slab, int K, int kc, int lr,
-                                            const unsigned char *cur, unsigned char *nxt, int frag_off,
+__device__ __forceinline__ void packed_slab(int ks, int last_slab, int K, uint32_t kcb,
+                                            uint32_t lds0, uint32_t lds_wave, uint32_t fo0,
                                             Streams &sm, const uint32_t (&xp)[NXF + RIDER],
                                             typename WFrag<W8>::type (&wq)[NGT][PW][2],
                                             typename WFrag<W8>::type (&wr)[RIDER ? rider_ring(NXF, W8) : 1][2],
-                                            u32x4_t (&XR)[NXF + RIDER], bf16x8_t (&X0)[NXF + RIDER],
+                                            bf16x8_t (&X0)[NXF + RIDER],
                                             bf16x8_t (&X1)[NXF + RIDER], f32x4_t (&acc)[NGT][2][2 * NXF],
                                             f32x4_t (&accr)[1][2][2]) {
+    constexpr int NXA = NXF + (RIDER ? 1 : 0);
+    constexpr int V = 2 * NGT + (RIDER ? 2 : 0);   // weight requests per step
     // contraction offsets past the row are clamped into it: the weights there are zero
     // (in bytes, like the row offsets xp)
-    const uint32_t koff = (uint32_t)min(min(ks + 2, last_slab) * 128 + kc * 16, K * 2 - 16);
-    unsigned char *xstage = nxt + lr * XROWB + kc * 16;
-    const unsigned char *xs = cur + frag_off;
-    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 0, 0, W8, RIDER, ONCE>(xs, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
-    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 1, -1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
-    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 0, 1, W8, RIDER, ONCE>(xs + 64, sm, wq, wr, X0, X1, acc, accr, xstage, XR, xp, koff);
+    const uint32_t koff = (uint32_t)min(min(ks + 2, last_slab) * 128 + (int)kcb, K * 2 - 16);
+    const uint32_t dma_lds = lds_wave + (uint32_t)((U + 2) % kStages * XSTAGEB);
+    const uint32_t cur = lds0 + U * XSTAGEB, nxt = lds0 + (U + 1) % kStages * XSTAGEB;
+    const uint32_t fo1 = fo0 ^ 64u;                // the same fragment of the slab's second step
+    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 0, 0, W8, RIDER, ONCE>(cur + fo0, sm, wq, wr, X0, X1, acc, accr, dma_lds, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 0) % PW, U * 2 + 0, PW, 1, -1, W8, RIDER, ONCE>(cur + fo1, sm, wq, wr, X1, X0, acc, accr, dma_lds, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 0, -1, W8, RIDER, ONCE>(cur + fo1, sm, wq, wr, X0, X1, acc, accr, dma_lds, xp, koff);
+    dma_wait<3 * V + NXA>();
     __syncthreads();
-    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 1, -1, W8, RIDER, ONCE>(nxt + frag_off, sm, wq, wr, X1, X0, acc, accr, xstage, XR, xp, koff);
+    packed_half<NXF, NGT, (U * 2 + 1) % PW, U * 2 + 1, PW, 1, -1, W8, RIDER, ONCE>(nxt + fo0, sm, wq, wr, X1, X0, acc, accr, dma_lds, xp, koff);
 }
 
 // Epilogue of 2 NF accumulator fragments of 16 rows x NGT column groups, which are the rows of
@@ -385,8 +417,15 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
     // register to spare, and come back from scratch inside every contraction loop.
     const int lane = lane_index(), wave = wave_id;
     const int tid = wave * 64 + lane;
-    const int lr = tid >> 3, kc = tid & 7;
-    const int frag_off = (lane & 15) * XROWB + (lane >> 4) * 16;
+    const int lr = tid >> 3;
+    // the lane's part in fetching a 32-row chunk: row lr of it, and the 16-byte piece of the slab
+    // that belongs at place (lane & 7) of that row in LDS
+    const uint32_t kcb = (uint32_t)(((lane & 7) ^ (lr & 7)) * 16);
+    // the lane's fragment reads: row (lane & 15) of a 16-row fragment, piece (lane >> 4) of the
+    // slab's first step where that row keeps it
+    const uint32_t fo0 = (uint32_t)((lane & 15) * XROWB + (((lane >> 4) ^ (lane & 7)) & 7) * 16);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const uint32_t lds_wave = lds0 + (uint32_t)__builtin_amdgcn_readfirstlane(wave * 8 * XROWB);
     const int ksteps = nk4 * 8;                    // 32-wide steps
     const int group0 = t.n0 / GC + wave * NGT;     // this wave's first column group
     const int group_r = r.n0 / GC + wave;          // and its one group of the rider
@@ -439,13 +478,12 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 #pragma unroll
             for (int g = 0; g < 2 * NXF; ++g) acc[n][h][g] = (f32x4_t)(0.0f);
 
-    // Request order: half the weight rings, the first two activation slabs, the other half of
-    // the rings.  The second slab is then followed by as many weight requests as in the loop,
-    // so the in-order load counter need not be drained when the loop is entered.
+    // Request order: half the weight rings, the first two activation slabs (into stages 0 and
+    // 1), the other half of the rings.  The first slab is complete once at most the requests
+    // issued after it are outstanding; the second is waited for in the first slab of the loop,
+    // which finds at least as many younger requests as any later slab does.
     F wq[NGT][PW][2], wr[RIDER ? RING_R : 1][2];
-    u32x4_t xr[NXA];
     {
-        u32x4_t xfirst[NXA];
 #pragma unroll
         for (int j = 0; j < PW / 2; ++j)
 #pragma unroll
@@ -458,11 +496,12 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 #pragma unroll
                 for (int h = 0; h < 2; ++h) wr[j][h] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep + h * 64 * (int)sizeof(F), sm.wlr);
         if (!RIDER) wr[0][0] = wr[0][1] = zero_fragment<W8>();    // placeholders that no MFMA reads
-        const uint32_t k0 = (uint32_t)min(kc * 16, K * 2 - 16), k1 = (uint32_t)min(128 + kc * 16, K * 2 - 16);
+        const uint32_t k0 = (uint32_t)min((int)kcb, K * 2 - 16), k1 = (uint32_t)min(128 + (int)kcb, K * 2 - 16);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < NXA; ++i) xfirst[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + k0);
+        for (int i = 0; i < NXA; ++i) dma_chunk(i < NXF ? sm.xb : sm.xbr, xp[i] + k0, lds_wave + 32 * i * XROWB);
 #pragma unroll
-        for (int i = 0; i < NXA; ++i) xr[i] = xload(i < NXF ? sm.xb : sm.xbr, xp[i] + k1);
+        for (int i = 0; i < NXA; ++i) dma_chunk(i < NXF ? sm.xb : sm.xbr, xp[i] + k1, lds_wave + XSTAGEB + 32 * i * XROWB);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int j = PW / 2; j < PW; ++j)
@@ -476,31 +515,26 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 #pragma unroll
                 for (int h = 0; h < 2; ++h) wr[j][h] = wload<true, F>(sm.wbr + (uint32_t)j * sm.wstep + h * 64 * (int)sizeof(F), sm.wlr);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NXA; ++i)
-            *reinterpret_cast<u32x4_t *>(smem + (lr + 32 * i) * XROWB + kc * 16) = xfirst[i];
+        dma_wait<NXA + (PW - PW / 2) * 2 * NGT + (RIDER ? (RING_R - RING_R / 2) * 2 : 0)>();
     }
     __syncthreads();
 
     // the lower fragments of the first step (the rider's 32 rows sit behind the tile's own)
     bf16x8_t x0[NXA], x1[NXA];
 #pragma unroll
-    for (int g = 0; g < NXF; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + g * 16 * XROWB);
-    if (RIDER) x0[NXA - 1] = *reinterpret_cast<const bf16x8_t *>(smem + frag_off + 32 * NXF * XROWB);
+    for (int g = 0; g < NXF; ++g) x0[g] = *reinterpret_cast<const bf16x8_t *>(smem + fo0 + g * 16 * XROWB);
+    if (RIDER) x0[NXA - 1] = *reinterpret_cast<const bf16x8_t *>(smem + fo0 + 32 * NXF * XROWB);
 
     const int last_slab = nk4 * 4 - 1;
-    // the three LDS stages, s0 the one of the current slab: four slabs on, the roles have moved by one
-    unsigned char *s0 = smem, *s1 = smem + XSTAGEB, *s2 = smem + 2 * XSTAGEB;
     for (int ks = 0; ks <= last_slab; ks += 4) {
-        packed_slab<NXF, NGT, 0, PW, W8, RIDER, ONCE>(ks + 0, last_slab, K, kc, lr, s0, s1, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 1, PW, W8, RIDER, ONCE>(ks + 1, last_slab, K, kc, lr, s1, s2, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 2, PW, W8, RIDER, ONCE>(ks + 2, last_slab, K, kc, lr, s2, s0, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
-        packed_slab<NXF, NGT, 3, PW, W8, RIDER, ONCE>(ks + 3, last_slab, K, kc, lr, s0, s1, frag_off, sm, xp, wq, wr, xr, x0, x1, acc, accr);
-        unsigned char *const s3 = s0;
-        s0 = s1;
-        s1 = s2;
-        s2 = s3;
+        packed_slab<NXF, NGT, 0, PW, W8, RIDER, ONCE>(ks + 0, last_slab, K, kcb, lds0, lds_wave, fo0, sm, xp, wq, wr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 1, PW, W8, RIDER, ONCE>(ks + 1, last_slab, K, kcb, lds0, lds_wave, fo0, sm, xp, wq, wr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 2, PW, W8, RIDER, ONCE>(ks + 2, last_slab, K, kcb, lds0, lds_wave, fo0, sm, xp, wq, wr, x0, x1, acc, accr);
+        packed_slab<NXF, NGT, 3, PW, W8, RIDER, ONCE>(ks + 3, last_slab, K, kcb, lds0, lds_wave, fo0, sm, xp, wq, wr, x0, x1, acc, accr);
     }
+    // the last slabs have requested rows past the end of the contraction (the last slab again):
+    // nothing may still be on its way into LDS when the tile, and perhaps the workgroup, ends
+    dma_wait<0>();
 
     // The next work item is claimed before the epilogue and looked at after it: the counter's
     // round trip runs while the results are converted and stored.
@@ -530,7 +564,7 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
 
 template <bool GATEUP, bool W8>
 __global__ __launch_bounds__(256, 1) void ffn_packed_kernel(FfnArgs a) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[3 * XSTAGEB];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kStages * XSTAGEB];
     __shared__ int64_t next_item;
     __shared__ TileTables tt;
     const int wave_id = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
