@@ -49,13 +49,13 @@
 namespace craft {
 namespace {
 
-// 32-wide weight steps kept in flight per column group: deep for the streaming-bound tiles with
-// few row fragments, shallower where the accumulators need the registers and each step carries
-// enough MFMA work to cover the latency.
-#ifndef RING_TALL
-#define RING_TALL 8
-#endif
-constexpr int ring_depth(int nxa) { return nxa >= 3 ? RING_TALL : 8; }
+// 32-wide weight steps kept in flight per column group.  Eight everywhere but in the tall tiles
+// of the down GEMM: its contraction is short, and what a deeper ring requests before the first
+// MFMA of a tile costs it more than the latency it covers (down GEMM at T = 32768: 438 -> 433 us).
+// The row requests, which the compiler does not count, sit between the weight requests: its
+// waits for a ring slot then wait for everything older as well, so a ring of eight steps covers
+// about four steps of latency.
+constexpr int ring_depth(int nxa, bool gateup) { return nxa >= 3 && !gateup ? 4 : 8; }
 // The rider's weights always come from HBM (nobody else reads them): where the registers are
 // there its ring runs twice as far ahead as the tile's own.
 constexpr int rider_ring(int nxf, bool w8) { return w8 || nxf <= 4 ? 8 : 4; }
@@ -410,7 +410,7 @@ __device__ __forceinline__ int32_t packed_tile(const FfnArgs &a, const Tile &t, 
                                                int wave_id) {
     constexpr int GC = GATEUP ? 16 : 32;
     constexpr int NXA = NXF + (RIDER ? 1 : 0);
-    constexpr int PW = ring_depth(NXA);
+    constexpr int PW = ring_depth(NXA, GATEUP);
     constexpr int RING_R = rider_ring(NXF, W8);
     // The lane's constants (LDS offsets and the like) are derived afresh in every tile: hoisted
     // out of the tile loop they would stay live through the tallest tile, which has no
