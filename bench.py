@@ -291,12 +291,12 @@ def copy_calibration(args):
 # (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
 # is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-_SHA = "7fa197998cc2d9de08fa89ff0cf2deb49dc90a291cadca89ce37693567f45930"
+_SHA = "8bbaea446a645cc925bd73ef6eb3d9202e06b4ae29262bbfeb395d4a51a2fb23"
 TRAFFIC = {
-    "qwen3": dict(fetch_kib=284626.4, write_kib=12742.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.403, mfma_busy_of_peak_clock=0.367, l2_to_cu_mb=1289.5, l2_hit=0.551, sources_sha256=_SHA),
-    "dsv3": dict(fetch_kib=197890.8, write_kib=9473.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.49, mfma_busy_of_peak_clock=0.431, l2_to_cu_mb=1537.9, l2_hit=0.735, sources_sha256=_SHA),
-    "kimi": dict(fetch_kib=177793.0, write_kib=10155.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.516, mfma_busy_of_peak_clock=0.448, l2_to_cu_mb=1404.2, l2_hit=0.739, sources_sha256=_SHA),
-    "stack": dict(fetch_kib=1004548.7, write_kib=75048.1, fetch_scale=2.0, write_scale=1.0, mfma_util=0.691, mfma_busy_of_peak_clock=0.538, l2_to_cu_mb=8886.6, l2_hit=0.761, sources_sha256=_SHA),
+    "qwen3": dict(fetch_kib=286706.9, write_kib=13510.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.42, mfma_busy_of_peak_clock=0.38, l2_to_cu_mb=1296.4, l2_hit=0.551, sources_sha256=_SHA),
+    "dsv3": dict(fetch_kib=195037.7, write_kib=10241.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.555, mfma_busy_of_peak_clock=0.477, l2_to_cu_mb=1545.1, l2_hit=0.74, sources_sha256=_SHA),
+    "kimi": dict(fetch_kib=163133.8, write_kib=10827.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.504, mfma_busy_of_peak_clock=0.44, l2_to_cu_mb=1413.5, l2_hit=0.762, sources_sha256=_SHA),
+    "stack": dict(fetch_kib=1050833.3, write_kib=75816.1, fetch_scale=2.0, write_scale=1.0, mfma_util=0.719, mfma_busy_of_peak_clock=0.55, l2_to_cu_mb=8925.2, l2_hit=0.749, sources_sha256=_SHA),
 }
 
 

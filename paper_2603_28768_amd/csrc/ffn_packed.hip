@@ -7,30 +7,34 @@
 // whatever the slot's row count.  What these kernels are built around:
 //
 //   * Expert weights are re-ordered once, outside the forward, into MFMA fragment order
-//     (craft_pack_weights): for each group of output columns and each 16-wide step of the
-//     contraction, the 32 x 16 block that one v_mfma_f32_32x32x16_bf16 consumes as its row
-//     operand is stored as 64 lanes x 16 bytes.  A wave reads its weights with one fully
-//     coalesced 1 KiB request per group and step, straight into registers: no LDS, no
-//     transposition, and the waves of a workgroup stream different column groups, so a
-//     workgroup requests no weight byte twice.  For gate/up a group interleaves 16 gate rows
-//     with the 16 up rows of the same output columns, which puts gate and up of one output
-//     into the same lane (accumulator elements v and v+8): SwiGLU is applied in registers.
+//     (craft_pack_weights): for each group of output columns and each 32-wide step of the
+//     contraction, the two 16 x 32 blocks that v_mfma_f32_16x16x32_bf16 consumes as its row
+//     operand are stored as 64 lanes x 16 bytes each.  A wave reads its weights with fully
+//     coalesced 1 KiB requests, straight into registers: no LDS, no transposition, and the
+//     waves of a workgroup stream different column groups, so a workgroup requests no weight
+//     byte twice.  For gate/up a group is the 16 gate rows of 16 output columns followed by
+//     the 16 up rows of the same columns, which puts gate and up of one output into the same
+//     lane and element of two accumulators: SwiGLU is applied in registers.
+//   * The 16 x 16 x 32 shape, because the matrix pipelines' power sets the clock: on operands
+//     like these a register-only loop of it sustains 2.05 PFLOP/s on this chip, one of
+//     32 x 32 x 16 1.76-1.84.
 //   * One workgroup of four waves per CU, one wave per SIMD, so a wave may use the whole
 //     512-entry register file: a tile is up to 256 activation rows x 8 column groups, each
-//     wave owning two groups x up to eight 32-row fragments (256 fp32 accumulators per
+//     wave owning two groups x up to sixteen 16-row fragments (256 fp32 accumulators per
 //     lane).  The large tile is what keeps the L2-to-CU traffic per flop low enough: a
 //     weight fragment loaded into a CU is used against 256 rows, an activation fragment
 //     against 128 (gate/up) or 256 (down) output columns.
-//   * The weight stream runs 8 or 16 steps ahead of the MFMAs in a statically indexed
-//     register ring (deeper for tiles with few rows); the activation rows (gathered through
-//     the dispatch permutation for gate/up) are shared by the four waves through LDS (three
-//     stages, one barrier per 64-wide slab), staged through registers a slab ahead.  The
-//     contraction loop has no branch around a memory operation, so the in-order load counter
-//     lets all of that stay in flight.
-//   * Under full load a CU gets about 45 GB/s out of L2 whatever it asks for, and a step moves
-//     8 KB of weights plus 1 KB per row fragment into it: at 256 x 256 the tile needs those
-//     bytes about as fast as the MFMAs consume them, below that it is bound by them.  Only
-//     fewer bytes per flop make it faster (8-bit weights); deeper rings do not.
+//   * The weight stream runs 4 or 8 steps ahead of the MFMAs in a statically indexed register
+//     ring; the activation rows (gathered through the dispatch permutation for gate/up) are
+//     shared by the four waves through LDS: four stages of one 64-wide slab, filled two slabs
+//     ahead by loads that write LDS directly (no registers, no LDS write instructions: those
+//     hand over four data registers per lane, which the MFMAs' own operand fetches leave no
+//     room for), one barrier per slab.  The contraction loop has no branch around a memory
+//     operation, so the in-order load counter lets all of that stay in flight.
+//   * Under full load a CU gets about 45 GB/s out of L2 whatever it asks for, and a 16-wide
+//     piece of the contraction moves 8 KB of weights plus 1 KB per 32 rows into it: at
+//     256 x 256 the tile needs those bytes about as fast as the MFMAs consume them, below that
+//     it is bound by them.
 //   * Weight fragments that a single tile reads (a cold slot's, a rider's, a busy slot's with
 //     one row-tile) are requested with streaming loads, so that the L2 keeps the activation
 //     rows and the weights that several tiles share.
