@@ -67,6 +67,11 @@ def check_matrix_operands(asm_path: str) -> int:
             if p.startswith("v_") and not p.startswith("v_mfma"):
                 if _registers(p.split(None, 1)[1].split(",")[0]) & src:
                     bad.append(f"{p}  ->  {t}")
+    # The loads that write LDS directly take their LDS address from M0, set by an asm statement of
+    # its own a few instructions earlier: nothing else in this code may touch M0.
+    other_m0 = [t for t in ins if re.search(r"\bm0\b", t) and not re.match(r"^s_mov_b32 m0, (s\d+|vcc_lo|vcc_hi|ttmp\d+)$", t.split(";")[0].strip())]
+    if other_m0:
+        raise RuntimeError(f"{asm_path}: M0 is used outside the row requests, e.g. {other_m0[0]}")
     if bad:
         raise RuntimeError(f"{asm_path}: {len(bad)} matrix instructions read a register written by one of the two "
                            "vector instructions in front of them, e.g.\n  " + "\n  ".join(bad[:5]))

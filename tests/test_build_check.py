@@ -30,3 +30,10 @@ def test_operands_from_loads_and_settled_vector_results_pass(tmp_path):
 def test_fresh_vector_results_are_caught(tmp_path, front):
     with pytest.raises(RuntimeError):
         _check(tmp_path, front + MFMA)
+
+
+def test_m0_belongs_to_the_row_requests(tmp_path):
+    ok = "\ts_mov_b32 m0, s12\n\tglobal_load_lds_dwordx4 v3, s[4:5]\n" + MFMA
+    assert _check(tmp_path, ok) == 1
+    with pytest.raises(RuntimeError):
+        _check(tmp_path, "\ts_mov_b32 m0, s12\n\tv_readlane_b32 s3, v9, m0\n" + MFMA)
