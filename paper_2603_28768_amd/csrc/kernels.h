@@ -35,8 +35,9 @@ constexpr int kColdRows = 64;
 // during a cold slot's tile it is the other way round.  So a tile of a busy slot carries a
 // "rider unit" along: one 32-row fragment of a cold slot against half a column tile of that
 // slot's weights (one column group per wave), streamed through a second weight ring and
-// costing one more MFMA per step.  Half a tile, not a whole one, because a CU's vector
-// memory path (64 bytes per clock) is already two-thirds used by the tile's own operands.
+// costing four more MFMAs of 16 x 16 x 32 per 32-wide step.  Half a tile, not a whole one,
+// because a CU's vector memory path (64 bytes per clock) is already two-thirds used by the
+// tile's own operands.
 // The units of the cold slots, in busiest-first order (two-fragment slots first), go to the
 // tiles of the list one each, from the first tile on: unit u rides on tile u.  A two-fragment
 // slot is carried whole or not at all.  Tiles of more than kRiderHostFrags fragments have no
